@@ -1,0 +1,154 @@
+/*
+ * cronus.h - C ABI of the MI355X (gfx950) mixed-iteration paged attention library.
+ *
+ * Scope: the attention work of one iteration of the chunked prefill instance of
+ * Cronus (arXiv 2509.17357).  In that system the first part of a prompt is
+ * prefilled on another GPU and its KV cache is transferred (section 4.2, steps 6-7:
+ * the transfer takes the place of computing that prefix); the remainder runs as
+ * chunked prefill, batched in the same iteration with single-token decodes of
+ * earlier requests (section 4.4, "Chunked prefill"; Eq. 3 names the two attention
+ * terms: continuation chunk against its prefill context, decodes against their
+ * contexts).  The cache is managed in blocks of N_size tokens (Algorithm 1).
+ *
+ * Two operations:
+ *   cronus_kv_append  - place K/V rows (a transferred prefix, or this iteration's new
+ *                       tokens) into paged blocks through a block table.
+ *   cronus_attn_mixed - causal attention of every sequence's chunk rows against
+ *                       all of its cached keys, chunks and decodes in one launch.
+ *
+ * General rules
+ *   - Every pointer says "host" or "device".  Device pointers are plain HIP device
+ *     addresses on the current device.  The caller owns every buffer; the library
+ *     never allocates or frees device memory and never allocates cache blocks.
+ *   - All device work is enqueued on `hip_stream` (a hipStream_t cast to void*; NULL
+ *     is the default stream).  No call synchronises the device.  Host arrays are
+ *     consumed before the call returns.
+ *   - Return value: a cronus_status.  Arguments are checked on the host before
+ *     anything is launched; on error nothing has been enqueued.
+ *   - Block ids in block tables are NOT checked on the device: an id outside
+ *     [0, num_blocks) or two rows mapped to one slot in a single call is undefined
+ *     behaviour.  Table entries past ceil(len/16) are never read and may hold
+ *     anything; cache slots past a sequence's length are never used as data.
+ *
+ * Paged cache layout (block_size = 16 tokens; E = element: bf16 = 2 bytes, or one
+ * fp8 e4m3 code = 1 byte).  The layout is chosen so that every MFMA operand of the
+ * attention kernel is one aligned 8-element chunk:
+ *   K pool: [num_blocks][Hkv][D/8][16][8] E
+ *       element (block b, head g, slot t, dim d) at
+ *       (((b*Hkv + g)*(D/8) + d/8)*16 + t)*8 + d%8
+ *       (a chunk = 8 consecutive d of one token; 16 tokens adjacent per chunk index)
+ *   V pool: [num_blocks][Hkv][2][D][8] E
+ *       element (b, g, t, d) at (((b*Hkv + g)*2 + t/8)*D + d)*8 + t%8
+ *       (a chunk = 8 consecutive tokens of one d)
+ *   One (block, head) is 16*D elements in either pool.
+ * fp8 pools: real value = code_value * scale[g], one fp32 scale per KV head for K
+ *   and one for V (OCP e4m3: no infinities, max 448).
+ */
+#ifndef CRONUS_H_
+#define CRONUS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CRONUS_OK = 0,
+  CRONUS_ERR_INVALID_ARG = 1, /* null pointer, negative size, lengths that do not fit the table */
+  CRONUS_ERR_UNSUPPORTED = 2, /* head_dim not 64/128, block_size != 16, Hq % Hkv != 0, unknown dtype */
+  CRONUS_ERR_WORKSPACE = 3,   /* workspace smaller than cronus_attn_mixed_workspace_bytes() */
+  CRONUS_ERR_HIP = 4          /* a HIP runtime call failed */
+} cronus_status;
+
+typedef enum { CRONUS_KV_BF16 = 0, CRONUS_KV_FP8_E4M3 = 1 } cronus_kv_dtype;
+
+typedef struct cronus_kv_cache {
+  void* k_cache;        /* device; K pool, layout above                                  */
+  void* v_cache;        /* device; V pool, layout above                                  */
+  const float* k_scale; /* device fp32 [Hkv]; must be NULL for bf16, non-NULL for fp8    */
+  const float* v_scale; /* device fp32 [Hkv]; same                                       */
+  int64_t num_blocks;   /* blocks in each pool                                           */
+  int32_t num_q_heads;  /* Hq                                                            */
+  int32_t num_kv_heads; /* Hkv, divides Hq; q head h reads kv head h / (Hq/Hkv)          */
+  int32_t head_dim;     /* D: 64 or 128                                                  */
+  int32_t block_size;   /* 16                                                            */
+  int32_t kv_dtype;     /* cronus_kv_dtype                                               */
+} cronus_kv_cache;
+
+/*
+ * cronus_kv_append - scatter K/V rows into their paged blocks.
+ * Section 4.2 (the transferred prefix is stored instead of computed) and the per-
+ * iteration append of ordinary chunked prefill / decode; block granularity from
+ * Algorithm 1.  Row r of sequence s (r = 0 .. cu_tokens[s+1]-cu_tokens[s]-1) is source
+ * row cu_tokens[s]+r and goes to logical position p = start_pos[s]+r, that is block
+ * block_tables[s*max_blocks_per_seq + p/16], slot p%16.  A prefix hand-off uses
+ * start_pos = 0; appending an iteration's new tokens uses start_pos = tokens already
+ * cached.  For an fp8 cache each element is quantised as
+ * e4m3_rne(clamp(fp32(x) / scale[g], -448, 448)) with one IEEE fp32 division.
+ *
+ *   k_src, v_src : device, bf16 [n_tokens][Hkv][D], rows of all sequences back to back
+ *   cu_tokens    : device, int32 [n_seqs+1], exclusive prefix sums, cu_tokens[0] = 0
+ *   start_pos    : device, int32 [n_seqs]
+ *   block_tables : device, int32 [n_seqs][max_blocks_per_seq]
+ *   n_tokens     : total rows (= cu_tokens[n_seqs]); 0 is a no-op
+ * Only the addressed slots are written.  The copy is bit-exact for bf16.
+ * Errors: INVALID_ARG (null pointer, negative count), UNSUPPORTED (shape/dtype).
+ */
+int cronus_kv_append(const cronus_kv_cache* cache, const void* k_src, const void* v_src,
+                     const int32_t* cu_tokens, const int32_t* start_pos,
+                     const int32_t* block_tables, int32_t max_blocks_per_seq, int32_t n_seqs,
+                     int32_t n_tokens, void* hip_stream);
+
+/*
+ * cronus_attn_mixed - attention of one mixed iteration (section 4.4; section 2 for
+ * decode as one token against the whole cache).  Sequence s contributes
+ * chunk_lens[s] query rows (1 = a decode, 0 = skipped) at logical positions
+ * prefix_lens[s] .. prefix_lens[s]+chunk_lens[s]-1; keys/values of positions
+ * [0, prefix_lens[s]+chunk_lens[s]) must already be in the cache.  Row i of head h:
+ *     out[i,h,:] = softmax_j(sm_scale * <q[i,h,:], K[j,h/G,:]>, j <= prefix+i) . V[:,h/G,:]
+ * computed with bf16 MFMA products, fp32 accumulation and fp32 softmax statistics;
+ * the result is rounded to bf16.
+ *
+ *   q, out       : device, bf16 [total_q][Hq][D], total_q = sum(chunk_lens), batch order
+ *   prefix_lens  : host, int32 [n_seqs]  (length already cached before this chunk)
+ *   chunk_lens   : host, int32 [n_seqs]
+ *   block_tables : device, int32 [n_seqs][max_blocks_per_seq]
+ *   sm_scale     : softmax scale, normally 1/sqrt(D)
+ *   workspace    : device, at least cronus_attn_mixed_workspace_bytes() bytes, 256-byte
+ *                  aligned; holds the work list and split partial results; contents
+ *                  are undefined afterwards; must not be shared by calls that can
+ *                  overlap on the device
+ * Errors: INVALID_ARG (null pointers, negative lengths, prefix+chunk >
+ * 16*max_blocks_per_seq), UNSUPPORTED, WORKSPACE, HIP.
+ */
+int cronus_attn_mixed(const cronus_kv_cache* cache, const void* q, void* out,
+                      const int32_t* prefix_lens, const int32_t* chunk_lens,
+                      const int32_t* block_tables, int32_t max_blocks_per_seq, int32_t n_seqs,
+                      float sm_scale, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of workspace cronus_attn_mixed needs for these lengths (host arrays); 0 on
+ * invalid arguments.  Depends only on the shapes and lengths, not on cache contents. */
+size_t cronus_attn_mixed_workspace_bytes(const cronus_kv_cache* cache, const int32_t* prefix_lens,
+                                         const int32_t* chunk_lens, int32_t n_seqs);
+
+/*
+ * cronus_attn_mixed_plan_stats - how the work decomposition (mixed batch of section
+ * 4.4 turned into tiles) would look for these lengths.  stats (host, int64[4]):
+ * [0] work items launched, [1] of those that are wide (chunk) tiles, [2] split partial
+ * results, [3] rows merged from partials.  Returns a cronus_status.
+ */
+int cronus_attn_mixed_plan_stats(const cronus_kv_cache* cache, const int32_t* prefix_lens,
+                                 const int32_t* chunk_lens, int32_t n_seqs, int64_t* stats);
+
+/* Static, NUL-terminated description of a cronus_status. */
+const char* cronus_status_string(int status);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int cronus_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CRONUS_H_ */

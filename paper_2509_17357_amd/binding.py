@@ -1,0 +1,142 @@
+"""ctypes binding of libcronus.so (include/cronus.h): argument marshalling only.
+
+Every step of the path runs in the HIP library; there is no CPU or PyTorch fallback.
+If the library has not been built, loading raises.  PyTorch is used by callers for
+device memory and streams; this module only reads `.data_ptr()`.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libcronus.so")
+
+CRONUS_OK = 0
+CRONUS_ERR_INVALID_ARG = 1
+CRONUS_ERR_UNSUPPORTED = 2
+CRONUS_ERR_WORKSPACE = 3
+CRONUS_ERR_HIP = 4
+CRONUS_KV_BF16 = 0
+CRONUS_KV_FP8_E4M3 = 1
+
+EXPORTS = ("cronus_kv_append", "cronus_attn_mixed", "cronus_attn_mixed_workspace_bytes",
+           "cronus_attn_mixed_plan_stats", "cronus_status_string", "cronus_version")
+
+
+class cronus_kv_cache(ctypes.Structure):
+    _fields_ = [("k_cache", ctypes.c_void_p), ("v_cache", ctypes.c_void_p),
+                ("k_scale", ctypes.c_void_p), ("v_scale", ctypes.c_void_p),
+                ("num_blocks", ctypes.c_int64),
+                ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("block_size", ctypes.c_int32),
+                ("kv_dtype", ctypes.c_int32)]
+
+
+class CronusError(RuntimeError):
+    def __init__(self, status, what):
+        super().__init__(f"{what}: {status_string(status)} (status {status})")
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it was never built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                               "`python -m paper_2509_17357_amd.build` (or __graft_entry__.build())")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i32p = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)
+        cp = ctypes.POINTER(cronus_kv_cache)
+        L.cronus_kv_append.argtypes = [cp, vp, vp, vp, vp, vp, i32, i32, i32, vp]
+        L.cronus_kv_append.restype = ctypes.c_int
+        L.cronus_attn_mixed.argtypes = [cp, vp, vp, i32p, i32p, vp, i32, i32, ctypes.c_float, vp, ctypes.c_size_t, vp]
+        L.cronus_attn_mixed.restype = ctypes.c_int
+        L.cronus_attn_mixed_workspace_bytes.argtypes = [cp, i32p, i32p, i32]
+        L.cronus_attn_mixed_workspace_bytes.restype = ctypes.c_size_t
+        L.cronus_attn_mixed_plan_stats.argtypes = [cp, i32p, i32p, i32, ctypes.POINTER(ctypes.c_int64)]
+        L.cronus_attn_mixed_plan_stats.restype = ctypes.c_int
+        L.cronus_status_string.argtypes = [ctypes.c_int]
+        L.cronus_status_string.restype = ctypes.c_char_p
+        L.cronus_version.argtypes = []
+        L.cronus_version.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().cronus_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return lib().cronus_version()
+
+
+def _ptr(t):
+    """Device/host address of a torch tensor, an int, or None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _host_i32(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def make_cache(k_cache, v_cache, num_blocks, num_q_heads, num_kv_heads, head_dim, kv_dtype=CRONUS_KV_BF16,
+               k_scale=None, v_scale=None, block_size=16) -> cronus_kv_cache:
+    return cronus_kv_cache(_ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale), int(num_blocks),
+                           int(num_q_heads), int(num_kv_heads), int(head_dim), int(block_size), int(kv_dtype))
+
+
+def cronus_kv_append(cache: cronus_kv_cache, k_src, v_src, cu_tokens, start_pos, block_tables,
+                     max_blocks_per_seq: int, n_seqs: int, n_tokens: int, stream: int = 0, check=True) -> int:
+    """k_src, v_src, cu_tokens, start_pos, block_tables: device tensors (or addresses)."""
+    rc = lib().cronus_kv_append(ctypes.byref(cache), _ptr(k_src), _ptr(v_src), _ptr(cu_tokens), _ptr(start_pos),
+                                _ptr(block_tables), int(max_blocks_per_seq), int(n_seqs), int(n_tokens),
+                                ctypes.c_void_p(stream))
+    if check and rc != CRONUS_OK:
+        raise CronusError(rc, "cronus_kv_append")
+    return rc
+
+
+def cronus_attn_mixed_workspace_bytes(cache: cronus_kv_cache, prefix_lens, chunk_lens) -> int:
+    p, pp = _host_i32(prefix_lens)
+    c, cp = _host_i32(chunk_lens)
+    return int(lib().cronus_attn_mixed_workspace_bytes(ctypes.byref(cache), pp, cp, int(p.size)))
+
+
+def cronus_attn_mixed_plan_stats(cache: cronus_kv_cache, prefix_lens, chunk_lens) -> dict:
+    p, pp = _host_i32(prefix_lens)
+    c, cp = _host_i32(chunk_lens)
+    st = (ctypes.c_int64 * 4)()
+    rc = lib().cronus_attn_mixed_plan_stats(ctypes.byref(cache), pp, cp, int(p.size), st)
+    if rc != CRONUS_OK:
+        raise CronusError(rc, "cronus_attn_mixed_plan_stats")
+    return {"items": st[0], "wide_items": st[1], "partials": st[2], "merge_rows": st[3]}
+
+
+def cronus_attn_mixed(cache: cronus_kv_cache, q, out, prefix_lens, chunk_lens, block_tables,
+                      max_blocks_per_seq: int, sm_scale: float, workspace, workspace_bytes: int,
+                      stream: int = 0, check=True) -> int:
+    """q, out, block_tables, workspace: device tensors; prefix_lens, chunk_lens: host int arrays."""
+    p, pp = _host_i32(prefix_lens)
+    c, cp = _host_i32(chunk_lens)
+    if p.size != c.size:
+        raise ValueError("prefix_lens and chunk_lens differ in length")
+    rc = lib().cronus_attn_mixed(ctypes.byref(cache), _ptr(q), _ptr(out), pp, cp, _ptr(block_tables),
+                                 int(max_blocks_per_seq), int(p.size), ctypes.c_float(sm_scale), _ptr(workspace),
+                                 ctypes.c_size_t(int(workspace_bytes)), ctypes.c_void_p(stream))
+    if check and rc != CRONUS_OK:
+        raise CronusError(rc, "cronus_attn_mixed")
+    return rc

@@ -1,0 +1,177 @@
+// C ABI entry points (include/cronus.h): argument checks, plan upload, launches.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <mutex>
+
+#include "cronus_internal.h"
+
+namespace cronus {
+namespace {
+
+int check_cache(const cronus_kv_cache* c) {
+  if (!c || !c->k_cache || !c->v_cache || c->num_blocks <= 0) return CRONUS_ERR_INVALID_ARG;
+  if (c->num_q_heads <= 0 || c->num_kv_heads <= 0) return CRONUS_ERR_INVALID_ARG;
+  if (c->block_size != kBlock) return CRONUS_ERR_UNSUPPORTED;
+  if (c->head_dim != 64 && c->head_dim != 128) return CRONUS_ERR_UNSUPPORTED;
+  if (c->num_q_heads % c->num_kv_heads) return CRONUS_ERR_UNSUPPORTED;
+  if (c->kv_dtype == CRONUS_KV_BF16) {
+    if (c->k_scale || c->v_scale) return CRONUS_ERR_INVALID_ARG;
+  } else if (c->kv_dtype == CRONUS_KV_FP8_E4M3) {
+    if (!c->k_scale || !c->v_scale) return CRONUS_ERR_INVALID_ARG;
+  } else {
+    return CRONUS_ERR_UNSUPPORTED;
+  }
+  return CRONUS_OK;
+}
+
+// Shape-only variant for the size queries, which need no device pointers.
+int check_shape(const cronus_kv_cache* c) {
+  if (!c || c->num_q_heads <= 0 || c->num_kv_heads <= 0) return CRONUS_ERR_INVALID_ARG;
+  if (c->block_size != kBlock) return CRONUS_ERR_UNSUPPORTED;
+  if (c->head_dim != 64 && c->head_dim != 128) return CRONUS_ERR_UNSUPPORTED;
+  if (c->num_q_heads % c->num_kv_heads) return CRONUS_ERR_UNSUPPORTED;
+  if (c->kv_dtype != CRONUS_KV_BF16 && c->kv_dtype != CRONUS_KV_FP8_E4M3) return CRONUS_ERR_UNSUPPORTED;
+  return CRONUS_OK;
+}
+
+int device_cus() {
+  static int cached = 0;
+  if (cached) return cached;
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) == hipSuccess &&
+      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) {
+    cached = n;
+  } else {
+    (void)hipGetLastError();
+    return 256;  // MI355X; used when sizes are queried without a device
+  }
+  return cached;
+}
+
+// Pinned host staging for the work list: the copy to the workspace is then a true
+// stream-ordered asynchronous copy.  A slot is reused only after its copy finished.
+struct Slot {
+  void* host = nullptr;
+  size_t cap = 0;
+  hipEvent_t done = nullptr;
+  bool pending = false;
+};
+constexpr int kSlots = 8;
+Slot g_slots[kSlots];
+int g_next = 0;
+std::mutex g_mu;
+
+Slot* acquire_slot(size_t bytes) {
+  Slot* s = &g_slots[g_next];
+  g_next = (g_next + 1) % kSlots;
+  if (s->pending) {
+    if (hipEventSynchronize(s->done) != hipSuccess) return nullptr;
+    s->pending = false;
+  }
+  if (s->cap < bytes) {
+    if (s->host) (void)hipHostFree(s->host);
+    s->host = nullptr;
+    s->cap = 0;
+    size_t cap = 1 << 16;
+    while (cap < bytes) cap <<= 1;
+    if (hipHostMalloc(&s->host, cap, hipHostMallocDefault) != hipSuccess) return nullptr;
+    s->cap = cap;
+  }
+  if (!s->done && hipEventCreateWithFlags(&s->done, hipEventDisableTiming) != hipSuccess) return nullptr;
+  return s;
+}
+
+}  // namespace
+}  // namespace cronus
+
+using namespace cronus;
+
+extern "C" {
+
+int cronus_kv_append(const cronus_kv_cache* cache, const void* k_src, const void* v_src,
+                     const int32_t* cu_tokens, const int32_t* start_pos, const int32_t* block_tables,
+                     int32_t max_blocks_per_seq, int32_t n_seqs, int32_t n_tokens, void* hip_stream) {
+  if (int rc = check_cache(cache)) return rc;
+  if (n_seqs < 0 || n_tokens < 0 || max_blocks_per_seq <= 0) return CRONUS_ERR_INVALID_ARG;
+  if (n_tokens == 0 || n_seqs == 0) return CRONUS_OK;
+  if (!k_src || !v_src || !cu_tokens || !start_pos || !block_tables) return CRONUS_ERR_INVALID_ARG;
+  return launch_kv_append(cache, k_src, v_src, cu_tokens, start_pos, block_tables, max_blocks_per_seq, n_seqs,
+                          n_tokens, hip_stream);
+}
+
+size_t cronus_attn_mixed_workspace_bytes(const cronus_kv_cache* cache, const int32_t* prefix_lens,
+                                         const int32_t* chunk_lens, int32_t n_seqs) {
+  if (check_shape(cache) || n_seqs < 0 || (n_seqs > 0 && (!prefix_lens || !chunk_lens))) return 0;
+  Plan plan;
+  if (build_plan(cache, prefix_lens, chunk_lens, n_seqs, 0x7fffffff / kBlock, device_cus(), &plan, nullptr)) return 0;
+  return plan.total_bytes;
+}
+
+int cronus_attn_mixed_plan_stats(const cronus_kv_cache* cache, const int32_t* prefix_lens,
+                                 const int32_t* chunk_lens, int32_t n_seqs, int64_t* stats) {
+  if (int rc = check_shape(cache)) return rc;
+  if (!stats || n_seqs < 0 || (n_seqs > 0 && (!prefix_lens || !chunk_lens))) return CRONUS_ERR_INVALID_ARG;
+  Plan plan;
+  if (int rc = build_plan(cache, prefix_lens, chunk_lens, n_seqs, 0x7fffffff / kBlock, device_cus(), &plan, nullptr))
+    return rc;
+  stats[0] = plan.n_items;
+  stats[1] = plan.n_wide;
+  stats[2] = plan.n_partials;
+  stats[3] = plan.n_merge_rows;
+  return CRONUS_OK;
+}
+
+int cronus_attn_mixed(const cronus_kv_cache* cache, const void* q, void* out, const int32_t* prefix_lens,
+                      const int32_t* chunk_lens, const int32_t* block_tables, int32_t max_blocks_per_seq,
+                      int32_t n_seqs, float sm_scale, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (int rc = check_cache(cache)) return rc;
+  if (n_seqs < 0 || max_blocks_per_seq <= 0) return CRONUS_ERR_INVALID_ARG;
+  if (!(sm_scale > 0.f) || !std::isfinite(sm_scale)) return CRONUS_ERR_INVALID_ARG;
+  if (n_seqs == 0) return CRONUS_OK;
+  if (!prefix_lens || !chunk_lens || !block_tables) return CRONUS_ERR_INVALID_ARG;
+  long long total_q = 0;
+  for (int s = 0; s < n_seqs; ++s) {
+    if (chunk_lens[s] < 0 || prefix_lens[s] < 0) return CRONUS_ERR_INVALID_ARG;
+    total_q += chunk_lens[s];
+  }
+  if (total_q == 0) return CRONUS_OK;
+  if (total_q > 0x7fffffffLL || !q || !out) return CRONUS_ERR_INVALID_ARG;
+
+  Plan plan;
+  const int n_cus = device_cus();
+  if (int rc = build_plan(cache, prefix_lens, chunk_lens, n_seqs, max_blocks_per_seq, n_cus, &plan, nullptr)) return rc;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return CRONUS_ERR_WORKSPACE;
+  if (workspace_bytes < plan.total_bytes) return CRONUS_ERR_WORKSPACE;
+  if (plan.n_items > 0x7fffffffLL) return CRONUS_ERR_INVALID_ARG;
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  {
+    std::lock_guard<std::mutex> lock(g_mu);
+    Slot* slot = acquire_slot(plan.upload_bytes);
+    if (!slot) return CRONUS_ERR_HIP;
+    if (int rc = build_plan(cache, prefix_lens, chunk_lens, n_seqs, max_blocks_per_seq, n_cus, &plan, slot->host))
+      return rc;
+    if (hipMemcpyAsync(workspace, slot->host, plan.upload_bytes, hipMemcpyHostToDevice, stream) != hipSuccess)
+      return CRONUS_ERR_HIP;
+    if (hipEventRecord(slot->done, stream) != hipSuccess) return CRONUS_ERR_HIP;
+    slot->pending = true;
+  }
+  AttnLaunch a{cache, q, out, block_tables, max_blocks_per_seq, sm_scale, workspace, &plan, hip_stream};
+  return launch_attn(a);
+}
+
+const char* cronus_status_string(int status) {
+  switch (status) {
+    case CRONUS_OK: return "ok";
+    case CRONUS_ERR_INVALID_ARG: return "invalid argument";
+    case CRONUS_ERR_UNSUPPORTED: return "unsupported shape or dtype";
+    case CRONUS_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case CRONUS_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int cronus_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,599 @@
+// Mixed-iteration attention for gfx950 (Cronus section 4.4: one iteration of the
+// chunked prefill instance batches a continuation chunk with decodes; Eq. 3 names
+// the two attention terms).  One launch runs every work item of the batch:
+//   wide item   - a tile of chunk rows (tokens x the q heads of one KV head) against
+//                 keys 0 .. its causal limit; K/V blocks are staged through LDS and
+//                 shared by the 4 waves, each wave owning 32*QT rows.
+//   narrow item - at most 32 rows (a decode, or a short chunk) against a span of
+//                 keys; the 4 waves split the span and stream K/V chunks straight
+//                 from the paged pools into MFMA operands; partial results of
+//                 spans are combined by the merge kernel.
+//
+// Both compute S^T = K Q^T and O^T = V^T P^T with v_mfma_f32_32x32x16_bf16, so a
+// lane owns one query row (column of S^T): its softmax statistics are lane-local
+// except for one exchange with lane^32.  The row order of the K operand is permuted
+// (perm32) so that the accumulators a lane holds after S^T are, in order, exactly
+// the 8-key chunks the P^T operand needs; the same permutation on the V^T operand
+// rows makes each lane own 8 consecutive output dims.
+#include <hip/hip_runtime.h>
+
+#include "cronus_internal.h"
+
+#ifndef CRONUS_WIDE_QT
+#define CRONUS_WIDE_QT 2
+#endif
+
+namespace cronus {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr float kNeg = -1.0e30f;  // initial running maximum: finite, so that differences of maxima stay finite
+
+struct AttnParams {
+  const unsigned short* q;
+  unsigned short* out;
+  const unsigned char* k_pool;
+  const unsigned char* v_pool;
+  const float* k_scale;
+  const float* v_scale;
+  const int* block_tables;
+  const SeqInfo* seqs;
+  const WorkItem* items;
+  const MergeItem* merges;
+  float* partials;
+  int max_blocks;
+  int n_q_heads;
+  int n_kv_heads;
+  float scale_log2e;  // sm_scale * log2(e)
+};
+
+// S^T row r of a 32-row MFMA tile holds key perm32(r) of the 32-key sub-tile
+// (bits 2 and 3 swapped), see the file comment.
+__device__ __forceinline__ int perm32(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
+
+// Combine a value with the one held by lane^32 (rows of 32 lanes swapped).
+__device__ __forceinline__ float pair_max(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float pair_sum(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+__device__ __forceinline__ unsigned int pack_bf16(float a, float b) {
+  f32x2 f = {a, b};
+  return __builtin_bit_cast(unsigned int, __builtin_convertvector(f, bf16x2));
+}
+
+// 8 e4m3 codes -> 8 bf16 (exact).
+__device__ __forceinline__ u32x4 fp8x8_to_bf16x8(u32x2 c) {
+  u32x4 r;
+  f32x2 f;
+  f = __builtin_amdgcn_cvt_pk_f32_fp8(c[0], false); r[0] = pack_bf16(f[0], f[1]);
+  f = __builtin_amdgcn_cvt_pk_f32_fp8(c[0], true);  r[1] = pack_bf16(f[0], f[1]);
+  f = __builtin_amdgcn_cvt_pk_f32_fp8(c[1], false); r[2] = pack_bf16(f[0], f[1]);
+  f = __builtin_amdgcn_cvt_pk_f32_fp8(c[1], true);  r[3] = pack_bf16(f[0], f[1]);
+  return r;
+}
+
+// Zero the elements e of a V chunk (8 consecutive keys kv0+e) whose key is >= kv_len:
+// slots past the sequence's length hold arbitrary bits and P = 0 there must give 0.
+__device__ __forceinline__ u32x4 zero_tail(u32x4 v, int kv0, int kv_len) {
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    unsigned int m = 0;
+    if (kv0 + 2 * w < kv_len) m |= 0x0000ffffu;
+    if (kv0 + 2 * w + 1 < kv_len) m |= 0xffff0000u;
+    v[w] &= m;
+  }
+  return v;
+}
+
+template <bool FP8> struct RawChunk { using type = u32x4; };
+template <> struct RawChunk<true> { using type = u32x2; };
+
+template <bool FP8>
+__device__ __forceinline__ typename RawChunk<FP8>::type load_chunk(const unsigned char* p) {
+  return *reinterpret_cast<const typename RawChunk<FP8>::type*>(p);
+}
+template <bool FP8>
+__device__ __forceinline__ u32x4 to_bf16_chunk(typename RawChunk<FP8>::type c) {
+  if constexpr (FP8) return fp8x8_to_bf16x8(c); else return c;
+}
+
+// Online softmax update of one 32(q) x 32(key) S^T tile held as 16 accumulators per
+// lane.  key of accumulator i = sub_base + 16*(i/8) + 8*half + i%8.
+// Returns the two P^T operands (keys 0-15 and 16-31 of the sub-tile).
+template <int NDB>
+__device__ __forceinline__ void softmax_tile(f32x16& s, bool need_mask, int sub_base, int half, int limit,
+                                             float c, float& m, float& l, f32x16 (&o)[NDB], u32x4 (&p)[2]) {
+  if (need_mask) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int kv = sub_base + 16 * (i >> 3) + 8 * half + (i & 7);
+      s[i] = kv > limit ? -__builtin_inff() : s[i];  // weight becomes exactly 0
+    }
+  }
+  float mx = s[0];
+#pragma unroll
+  for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i]);
+  mx = pair_max(mx);
+  const float m_new = fmaxf(m, mx);
+  if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {  // wave-uniform: some row's maximum grew
+    const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
+    l *= alpha;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+    m = m_new;
+  }
+  const float mc = m * c;
+  float sum = 0.f;
+  float e[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    e[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c, -mc));
+    sum += e[i];
+  }
+  l += sum;
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int w = 0; w < 4; ++w) p[t][w] = pack_bf16(e[8 * t + 2 * w], e[8 * t + 2 * w + 1]);
+}
+
+// Store one lane's share of a finished row: dims 32*db + 16*j + 8*half + 0..7.
+template <int NDB>
+__device__ __forceinline__ void store_row_bf16(unsigned short* row_ptr, const f32x16 (&o)[NDB], float mul, int half) {
+#pragma unroll
+  for (int db = 0; db < NDB; ++db)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      u32x4 w;
+#pragma unroll
+      for (int x = 0; x < 4; ++x) w[x] = pack_bf16(o[db][8 * j + 2 * x] * mul, o[db][8 * j + 2 * x + 1] * mul);
+      *reinterpret_cast<u32x4*>(row_ptr + 32 * db + 16 * j + 8 * half) = w;
+    }
+}
+
+// ------------------------------------------------------------------ wide (chunk) tile
+template <int D, bool FP8, int QT>
+__device__ __forceinline__ void run_wide(const AttnParams& p, const WorkItem& it, unsigned char* smem) {
+  constexpr int NSTEP = D / 16, NDB = D / 32;
+  constexpr int BLK_LDS = 16 * D * 2;           // bytes of one (block, head) as bf16
+  constexpr int KT_BYTES = 4 * BLK_LDS;         // K (or V) tile: 64 keys
+  constexpr int STAGE = 2 * KT_BYTES;
+  constexpr int CH_PER_BLK = 2 * D;             // 8-element chunks per (block, head)
+  constexpr int PER = D / 32;                   // chunks of K (and of V) each thread stages
+  constexpr int ESZ = FP8 ? 1 : 2;
+  using Raw = typename RawChunk<FP8>::type;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, half = lane >> 5, c32 = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const SeqInfo si = p.seqs[it.seq];
+  const int gi_n = it.n_heads;
+  const int rows_valid = it.n_tok * gi_n;
+  const int row_base = wave * 32 * QT;
+  const bool wave_active = row_base < rows_valid;
+  const int kv_len = si.prefix_len + si.chunk_len;
+  const int pos0 = si.prefix_len + it.q_tok0;   // absolute position of the tile's first token
+  const float c = p.scale_log2e * (FP8 ? p.k_scale[it.kv_head] : 1.0f);
+
+  // causal limits of the rows this wave owns (rows past the tile repeat the last row)
+  const int wave_min_limit = pos0 + min(row_base, rows_valid - 1) / gi_n;
+  const int wave_max_limit = pos0 + min(row_base + 32 * QT - 1, rows_valid - 1) / gi_n;
+
+  bf16x8 qreg[QT][NSTEP];
+  int limit[QT];
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt) {
+    const int r = min(row_base + qt * 32 + c32, rows_valid - 1);
+    const int t = r / gi_n, gi = r - t * gi_n;
+    limit[qt] = pos0 + t;
+    const unsigned short* qp =
+        p.q + ((long long)(si.q_off + it.q_tok0 + t) * p.n_q_heads + it.head0 + gi) * D + 8 * half;
+#pragma unroll
+    for (int s = 0; s < NSTEP; ++s) qreg[qt][s] = as_bf16x8(*reinterpret_cast<const u32x4*>(qp + 16 * s));
+  }
+
+  f32x16 o[QT][NDB];
+  float m[QT], l[QT];
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt) {
+    m[qt] = kNeg;
+    l[qt] = 0.f;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[qt][db][i] = 0.f;
+  }
+
+  const int* bt = p.block_tables + (long long)it.seq * p.max_blocks;
+  const long long head_stride = (long long)16 * D * ESZ;  // bytes of one (block, head)
+  const int n_tiles = (it.kv_end - it.kv_begin + kWideKvTile - 1) / kWideKvTile;
+
+  Raw rk[PER], rv[PER];
+  auto stage_load = [&](int tile_base) {
+#pragma unroll
+    for (int n = 0; n < PER; ++n) {
+      const int id = tid + kThreads * n;
+      const int blk = id / CH_PER_BLK, off = id - blk * CH_PER_BLK;
+      const int bidx = (tile_base >> 4) + blk;
+      if (bidx < si.n_blocks) {
+        const long long base = ((long long)bt[bidx] * p.n_kv_heads + it.kv_head) * head_stride + (long long)off * 8 * ESZ;
+        rk[n] = load_chunk<FP8>(p.k_pool + base);
+        rv[n] = load_chunk<FP8>(p.v_pool + base);
+      } else {
+        rk[n] = Raw(0);
+        rv[n] = Raw(0);
+      }
+    }
+  };
+  auto stage_store = [&](int buf, int tile_base) {
+    unsigned char* kb = smem + buf * STAGE;
+    unsigned char* vb = kb + KT_BYTES;
+    const bool tail = tile_base + kWideKvTile > kv_len;
+#pragma unroll
+    for (int n = 0; n < PER; ++n) {
+      const int id = tid + kThreads * n;
+      u32x4 kk = to_bf16_chunk<FP8>(rk[n]);
+      u32x4 vv = to_bf16_chunk<FP8>(rv[n]);
+      if (tail) {
+        const int blk = id / CH_PER_BLK, off = id - blk * CH_PER_BLK;
+        vv = zero_tail(vv, tile_base + 16 * blk + 8 * (off / D), kv_len);
+      }
+      *reinterpret_cast<u32x4*>(kb + id * 16) = kk;
+      *reinterpret_cast<u32x4*>(vb + id * 16) = vv;
+    }
+  };
+
+  const int pr = perm32(c32);
+  // byte offset of this lane's K chunk (step 0) inside a 32-key sub-tile, and of its V chunk (db 0)
+  const int k_lane_off = (pr >> 4) * BLK_LDS + (half * 16 + (pr & 15)) * 16;
+  const int v_lane_off = (half * D + pr) * 16;
+
+  stage_load(it.kv_begin);
+  int buf = 0;
+  for (int j = 0; j < n_tiles; ++j) {
+    const int tile_base = it.kv_begin + j * kWideKvTile;
+    stage_store(buf, tile_base);
+    __syncthreads();
+    if (j + 1 < n_tiles) stage_load(tile_base + kWideKvTile);
+    if (wave_active && tile_base <= wave_max_limit) {
+      const unsigned char* kb = smem + buf * STAGE;
+      const unsigned char* vb = kb + KT_BYTES;
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int sub_base = tile_base + 32 * u;
+        if (sub_base > wave_max_limit) break;
+        const bool need_mask = sub_base + 31 > wave_min_limit;
+        f32x16 s[QT];
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) s[qt][i] = 0.f;
+        const unsigned char* ksub = kb + u * 2 * BLK_LDS + k_lane_off;
+#pragma unroll
+        for (int st = 0; st < NSTEP; ++st) {
+          const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(ksub + st * 512));
+#pragma unroll
+          for (int qt = 0; qt < QT; ++qt)
+            s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qt][st], s[qt], 0, 0, 0);
+        }
+        u32x4 pp[QT][2];
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt)
+          softmax_tile<NDB>(s[qt], need_mask, sub_base, half, limit[qt], c, m[qt], l[qt], o[qt], pp[qt]);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const unsigned char* vsub = vb + (u * 2 + t) * BLK_LDS + v_lane_off;
+#pragma unroll
+          for (int db = 0; db < NDB; ++db) {
+            const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(vsub + db * 512));
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt)
+              o[qt][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, as_bf16x8(pp[qt][t]), o[qt][db], 0, 0, 0);
+          }
+        }
+      }
+    }
+    buf ^= 1;
+  }
+
+  // epilogue: normalise and store (wide items are never split)
+  const float vmul = FP8 ? p.v_scale[it.kv_head] : 1.0f;
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt) {
+    const int r = row_base + qt * 32 + c32;
+    const float lt = pair_sum(l[qt]);
+    if (r < rows_valid) {
+      const int t = r / gi_n, gi = r - t * gi_n;
+      unsigned short* op = p.out + ((long long)(si.q_off + it.q_tok0 + t) * p.n_q_heads + it.head0 + gi) * D;
+      store_row_bf16<NDB>(op, o[qt], vmul / lt, half);
+    }
+  }
+}
+
+// --------------------------------------------------------- narrow (decode-like) item
+template <int D, bool FP8>
+struct NarrowOps {
+  typename RawChunk<FP8>::type k[D / 16];
+  typename RawChunk<FP8>::type v[2 * (D / 32)];
+};
+
+template <int D, bool FP8>
+__device__ __forceinline__ void run_narrow(const AttnParams& p, const WorkItem& it, unsigned char* smem) {
+  constexpr int NSTEP = D / 16, NDB = D / 32;
+  constexpr int ESZ = FP8 ? 1 : 2;
+  constexpr int NACC = NDB * 16;
+  using Raw = typename RawChunk<FP8>::type;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, half = lane >> 5, c32 = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const SeqInfo si = p.seqs[it.seq];
+  const int gi_n = it.n_heads;
+  const int rows_valid = it.n_tok * gi_n;  // <= 32
+  const int kv_len = si.prefix_len + si.chunk_len;
+  const int pos0 = si.prefix_len + it.q_tok0;
+  const float c = p.scale_log2e * (FP8 ? p.k_scale[it.kv_head] : 1.0f);
+  const int min_limit = pos0;
+
+  const int r = min(c32, rows_valid - 1);
+  const int t_row = r / gi_n, gi_row = r - t_row * gi_n;
+  const int limit = pos0 + t_row;
+  bf16x8 qreg[NSTEP];
+  {
+    const unsigned short* qp =
+        p.q + ((long long)(si.q_off + it.q_tok0 + t_row) * p.n_q_heads + it.head0 + gi_row) * D + 8 * half;
+#pragma unroll
+    for (int s = 0; s < NSTEP; ++s) qreg[s] = as_bf16x8(*reinterpret_cast<const u32x4*>(qp + 16 * s));
+  }
+
+  f32x16 o[NDB];
+  float m = kNeg, l = 0.f;
+#pragma unroll
+  for (int db = 0; db < NDB; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
+
+  const int* bt = p.block_tables + (long long)it.seq * p.max_blocks;
+  const long long head_stride = (long long)16 * D * ESZ;
+  const int n_sub = (it.kv_end - it.kv_begin + 31) >> 5;
+  const int pr = perm32(c32);
+  const long long k_lane_off = (long long)(half * 16 + (pr & 15)) * 8 * ESZ;
+  const long long v_lane_off = (long long)(half * D + pr) * 8 * ESZ;
+
+  auto load_ops = [&](NarrowOps<D, FP8>& ops, int u) {
+    if (u >= n_sub) return;
+    const int blk0 = (it.kv_begin + 32 * u) >> 4;
+    const int kb = blk0 + (pr >> 4);
+    if (kb < si.n_blocks) {
+      const unsigned char* kp = p.k_pool + ((long long)bt[kb] * p.n_kv_heads + it.kv_head) * head_stride + k_lane_off;
+#pragma unroll
+      for (int s = 0; s < NSTEP; ++s) ops.k[s] = load_chunk<FP8>(kp + s * (256 * ESZ));
+    } else {
+#pragma unroll
+      for (int s = 0; s < NSTEP; ++s) ops.k[s] = Raw(0);
+    }
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      if (blk0 + t < si.n_blocks) {
+        const unsigned char* vp =
+            p.v_pool + ((long long)bt[blk0 + t] * p.n_kv_heads + it.kv_head) * head_stride + v_lane_off;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) ops.v[t * NDB + db] = load_chunk<FP8>(vp + db * (256 * ESZ));
+      } else {
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) ops.v[t * NDB + db] = Raw(0);
+      }
+    }
+  };
+
+  auto process = [&](const NarrowOps<D, FP8>& ops, int u) {
+    const int sub_base = it.kv_begin + 32 * u;
+    f32x16 s;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s[i] = 0.f;
+#pragma unroll
+    for (int st = 0; st < NSTEP; ++st)
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(to_bf16_chunk<FP8>(ops.k[st])), qreg[st], s, 0, 0, 0);
+    u32x4 pp[2];
+    softmax_tile<NDB>(s, sub_base + 31 > min_limit, sub_base, half, limit, c, m, l, o, pp);
+    const bool tail = sub_base + 32 > kv_len;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) {
+        u32x4 vv = to_bf16_chunk<FP8>(ops.v[t * NDB + db]);
+        if (tail) vv = zero_tail(vv, sub_base + 16 * t + 8 * half, kv_len);
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vv), as_bf16x8(pp[t]), o[db], 0, 0, 0);
+      }
+  };
+
+  // three operand sets in flight per wave: wave w takes sub-tiles w, w+4, w+8, ...
+  NarrowOps<D, FP8> a, b, cc;
+  load_ops(a, wave);
+  load_ops(b, wave + kWaves);
+  for (int u = wave; u < n_sub; u += 3 * kWaves) {
+    load_ops(cc, u + 2 * kWaves);
+    process(a, u);
+    if (u + kWaves < n_sub) {
+      load_ops(a, u + 3 * kWaves);
+      process(b, u + kWaves);
+    }
+    if (u + 2 * kWaves < n_sub) {
+      load_ops(b, u + 4 * kWaves);
+      process(cc, u + 2 * kWaves);
+    }
+  }
+
+  // combine the four waves (each covered different keys) in wave 0
+  float* xch = reinterpret_cast<float*>(smem);  // [3][NACC + 2][64]
+  if (wave > 0) {
+    float* w = xch + (wave - 1) * (NACC + 2) * 64 + lane;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) w[(db * 16 + i) * 64] = o[db][i];
+    w[NACC * 64] = m;
+    w[(NACC + 1) * 64] = l;
+  }
+  __syncthreads();
+  if (wave == 0) {
+#pragma unroll 1
+    for (int w2 = 0; w2 < kWaves - 1; ++w2) {
+      const float* w = xch + w2 * (NACC + 2) * 64 + lane;
+      const float mo = w[NACC * 64], lo = w[(NACC + 1) * 64];
+      const float mn = fmaxf(m, mo);
+      const float a0 = __builtin_amdgcn_exp2f((m - mn) * c), a1 = __builtin_amdgcn_exp2f((mo - mn) * c);
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[db][i] = o[db][i] * a0 + w[(db * 16 + i) * 64] * a1;
+      l = l * a0 + lo * a1;
+      m = mn;
+    }
+    float lt = pair_sum(l);
+    if (m <= kNeg) {  // no visible key in this span for this row
+      lt = 0.f;
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
+    }
+    if (c32 < rows_valid) {
+      if (it.partial < 0) {
+        const float vmul = FP8 ? p.v_scale[it.kv_head] : 1.0f;
+        unsigned short* op =
+            p.out + ((long long)(si.q_off + it.q_tok0 + t_row) * p.n_q_heads + it.head0 + gi_row) * D;
+        store_row_bf16<NDB>(op, o, vmul / lt, half);
+      } else {
+        float* ps = p.partials + (long long)it.partial * (kNarrowRows * (D + 2));
+        float* orow = ps + c32 * D;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+            f32x4 lo4 = {o[db][8 * j], o[db][8 * j + 1], o[db][8 * j + 2], o[db][8 * j + 3]};
+            f32x4 hi4 = {o[db][8 * j + 4], o[db][8 * j + 5], o[db][8 * j + 6], o[db][8 * j + 7]};
+            float* dp = orow + 32 * db + 16 * j + 8 * half;
+            *reinterpret_cast<f32x4*>(dp) = lo4;
+            *reinterpret_cast<f32x4*>(dp + 4) = hi4;
+          }
+        if (half == 0) {
+          ps[kNarrowRows * D + c32] = m * c;  // running maximum in log2 units
+          ps[kNarrowRows * D + kNarrowRows + c32] = lt;
+        }
+      }
+    }
+  }
+}
+
+template <int D, bool FP8, int QT>
+__global__ __launch_bounds__(kThreads) void attn_mixed_kernel(AttnParams p) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const WorkItem it = p.items[blockIdx.x];
+  if (it.wide) run_wide<D, FP8, QT>(p, it, smem);
+  else run_narrow<D, FP8>(p, it, smem);
+}
+
+// Combine the partial results of a row group that was split over key spans:
+// out = sum_s O_s 2^(m_s - M) / sum_s l_s 2^(m_s - M), M = max_s m_s (m in log2 units).
+template <int D, bool FP8>
+__global__ __launch_bounds__(D) void attn_merge_kernel(AttnParams p) {
+  const MergeItem mi = p.merges[blockIdx.x];
+  const SeqInfo si = p.seqs[mi.seq];
+  const int d = threadIdx.x;
+  const int rows = mi.n_tok * mi.n_heads;
+  const size_t slot = (size_t)kNarrowRows * (D + 2);
+  const float vmul = FP8 ? p.v_scale[mi.kv_head] : 1.0f;
+  for (int r = 0; r < rows; ++r) {
+    const float* base = p.partials + (size_t)mi.first_partial * slot;
+    float mt = kNeg * 4.f;
+    for (int s = 0; s < mi.n_split; ++s) mt = fmaxf(mt, base[s * slot + kNarrowRows * D + r]);
+    float acc = 0.f, ls = 0.f;
+    for (int s = 0; s < mi.n_split; ++s) {
+      const float* ps = base + s * slot;
+      const float w = __builtin_amdgcn_exp2f(ps[kNarrowRows * D + r] - mt);
+      acc += ps[r * D + d] * w;
+      ls += ps[kNarrowRows * D + kNarrowRows + r] * w;
+    }
+    const int t = r / mi.n_heads, gi = r - t * mi.n_heads;
+    unsigned short* op = p.out + ((long long)(si.q_off + mi.q_tok0 + t) * p.n_q_heads + mi.head0 + gi) * D;
+    const __bf16 v = (__bf16)(acc * vmul / ls);
+    op[d] = __builtin_bit_cast(unsigned short, v);
+  }
+}
+
+template <int D, bool FP8>
+int launch_typed(const AttnLaunch& a, const AttnParams& p) {
+  constexpr int QT = CRONUS_WIDE_QT;
+  constexpr int wide_lds = 2 * 2 * 4 * 16 * D * 2;
+  constexpr int narrow_lds = 3 * ((D / 32) * 16 + 2) * 64 * 4;
+  constexpr int lds = wide_lds > narrow_lds ? wide_lds : narrow_lds;
+  static_assert(lds <= 160 * 1024, "LDS budget");
+  hipStream_t s = static_cast<hipStream_t>(a.stream);
+  const Plan& pl = *a.plan;
+  if (pl.n_items > 0) {
+    auto kern = attn_mixed_kernel<D, FP8, QT>;
+    static bool attr_set = false;
+    if (!attr_set) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
+          hipSuccess)
+        return CRONUS_ERR_HIP;
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)pl.n_items), dim3(kThreads), lds, s, p);
+    if (hipGetLastError() != hipSuccess) return CRONUS_ERR_HIP;
+  }
+  if (pl.n_merge > 0) {
+    hipLaunchKernelGGL((attn_merge_kernel<D, FP8>), dim3((unsigned)pl.n_merge), dim3(D), 0, s, p);
+    if (hipGetLastError() != hipSuccess) return CRONUS_ERR_HIP;
+  }
+  return CRONUS_OK;
+}
+
+}  // namespace
+
+int wide_rows_for(int /*head_dim*/, int /*kv_dtype*/) { return kWaves * 32 * CRONUS_WIDE_QT; }
+
+int launch_attn(const AttnLaunch& a) {
+  const cronus_kv_cache& c = *a.cache;
+  const Plan& pl = *a.plan;
+  unsigned char* ws = static_cast<unsigned char*>(a.workspace);
+  AttnParams p;
+  p.q = static_cast<const unsigned short*>(a.q);
+  p.out = static_cast<unsigned short*>(a.out);
+  p.k_pool = static_cast<const unsigned char*>(c.k_cache);
+  p.v_pool = static_cast<const unsigned char*>(c.v_cache);
+  p.k_scale = c.k_scale;
+  p.v_scale = c.v_scale;
+  p.block_tables = a.block_tables;
+  p.seqs = reinterpret_cast<const SeqInfo*>(ws + pl.off_seqs);
+  p.items = reinterpret_cast<const WorkItem*>(ws + pl.off_items);
+  p.merges = reinterpret_cast<const MergeItem*>(ws + pl.off_merge);
+  p.partials = reinterpret_cast<float*>(ws + pl.off_partials);
+  p.max_blocks = a.max_blocks_per_seq;
+  p.n_q_heads = c.num_q_heads;
+  p.n_kv_heads = c.num_kv_heads;
+  p.scale_log2e = a.sm_scale * 1.4426950408889634f;
+  const bool fp8 = c.kv_dtype == CRONUS_KV_FP8_E4M3;
+  if (c.head_dim == 128) return fp8 ? launch_typed<128, true>(a, p) : launch_typed<128, false>(a, p);
+  if (c.head_dim == 64) return fp8 ? launch_typed<64, true>(a, p) : launch_typed<64, false>(a, p);
+  return CRONUS_ERR_UNSUPPORTED;
+}
+
+}  // namespace cronus

@@ -1,0 +1,92 @@
+// Internal declarations shared by the host planner, the launchers and the kernels.
+// Not part of the public ABI (that is include/cronus.h).
+#pragma once
+
+#include <stddef.h>
+#include <stdint.h>
+
+#include "cronus.h"
+
+namespace cronus {
+
+constexpr int kBlock = 16;          // tokens per KV block (N_size of Algorithm 1)
+constexpr int kThreads = 256;       // 4 wavefronts of 64 lanes per work-group
+constexpr int kWaves = 4;
+constexpr int kNarrowRows = 32;     // one MFMA column tile: a decode's (token, head) rows
+constexpr int kWideKvTile = 64;     // keys staged in LDS per step of a wide (chunk) tile
+constexpr int kNarrowKvStep = 32 * kWaves;  // keys covered by the 4 waves of a narrow item per step
+
+// Per-sequence record of the batch (section 4.4: one iteration = chunks + decodes).
+struct SeqInfo {
+  int32_t prefix_len;  // keys cached before this chunk ("length already processed", section 4.2)
+  int32_t chunk_len;   // query rows of this iteration (1 = decode)
+  int32_t q_off;       // index of the sequence's first row in q/out
+  int32_t n_blocks;    // ceil((prefix+chunk)/16): table entries that may be read
+};
+
+// One work-group's job.
+struct WorkItem {
+  int32_t seq;
+  int32_t kv_head;
+  int32_t head0;     // first q head of the group handled here
+  int32_t n_heads;   // q heads handled (all read kv_head)
+  int32_t q_tok0;    // first chunk token of the tile
+  int32_t n_tok;     // tokens in the tile; rows = n_tok * n_heads
+  int32_t kv_begin;  // keys [kv_begin, kv_end) are processed by this item
+  int32_t kv_end;
+  int32_t partial;   // < 0: writes final output; else index of its partial-result slot
+  int32_t wide;      // 1: chunk tile staged through LDS; 0: narrow (<= 32 rows), waves split keys
+  int32_t pad0, pad1;
+};
+
+// Rows whose partial results (split over key spans) are combined by the merge kernel.
+struct MergeItem {
+  int32_t first_partial;
+  int32_t n_split;
+  int32_t seq;
+  int32_t kv_head;
+  int32_t head0;
+  int32_t n_heads;
+  int32_t q_tok0;
+  int32_t n_tok;
+};
+
+struct Plan {
+  // sizes
+  int64_t n_items = 0, n_wide = 0, n_partials = 0, n_merge = 0, n_merge_rows = 0;
+  int32_t n_seqs = 0;
+  int32_t wide_rows = 0;  // rows per wide tile (compile-time choice of the kernel instance)
+  // byte offsets inside the workspace
+  size_t off_seqs = 0, off_items = 0, off_merge = 0, off_partials = 0, total_bytes = 0;
+  size_t upload_bytes = 0;  // [0, upload_bytes) is host-built metadata
+};
+
+// Number of floats of one partial slot: O[32][D], m[32], l[32].
+inline size_t partial_floats(int head_dim) { return (size_t)kNarrowRows * (head_dim + 2); }
+
+// Rows per wide tile for a head shape (must match the kernel instance that is launched).
+int wide_rows_for(int head_dim, int kv_dtype);
+
+// Builds the work decomposition.  If `host_buf` is null only sizes are computed.
+// `host_buf` must hold plan->upload_bytes bytes (call once with null to learn it).
+int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const int32_t* chunk_lens,
+               int32_t n_seqs, int32_t max_blocks_per_seq, int n_cus, Plan* plan, void* host_buf);
+
+struct AttnLaunch {
+  const cronus_kv_cache* cache;
+  const void* q;
+  void* out;
+  const int32_t* block_tables;
+  int32_t max_blocks_per_seq;
+  float sm_scale;
+  void* workspace;  // device; metadata already uploaded
+  const Plan* plan;
+  void* stream;
+};
+
+int launch_attn(const AttnLaunch& a);
+int launch_kv_append(const cronus_kv_cache* cache, const void* k_src, const void* v_src,
+                     const int32_t* cu_tokens, const int32_t* start_pos, const int32_t* block_tables,
+                     int32_t max_blocks_per_seq, int32_t n_seqs, int32_t n_tokens, void* stream);
+
+}  // namespace cronus

@@ -1,0 +1,137 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 oracle, element by
+element, on the same seeded inputs.  Scatter must be bit-exact; attention within
+max-abs 2e-2 and relative L2 1e-2 (overall, per sequence, chunk rows, decode rows)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2509_17357_amd import binding as B
+from paper_2509_17357_amd import workloads as W
+from paper_2509_17357_amd.runtime import DeviceIteration, bits_from_bf16_tensor
+
+import parity_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+def run_batch(batch, poison=True, check_pools=True, scales=None):
+    """Full hot path on the GPU + oracle on the host; returns the error report."""
+    fill = 0x7FC1 if batch.shape.kv_dtype == "bf16" else 0x7F  # NaN patterns in unused slots
+    it = DeviceIteration(batch, pool_fill=(fill if fill < 0x8000 else fill - 0x10000) if poison else 0)
+    kv_bits = it.load_host_inputs()
+    ks = vs = None
+    if it.fp8:
+        ks, vs = scales if scales is not None else it.amax_scales()
+        it.set_fp8_scales(ks, vs)
+    it.step()
+    torch.cuda.synchronize()
+    if check_pools:
+        kp, vp = U.oracle_pools(batch, kv_bits, fill=fill, k_scale=ks, v_scale=vs)
+        view = (lambda t: t.cpu().numpy()) if it.fp8 else (lambda t: t.cpu().numpy().view(np.uint16))
+        assert np.array_equal(view(it.k_pool), kp), "K pool differs from the reference scatter"
+        assert np.array_equal(view(it.v_pool), vp), "V pool differs from the reference scatter"
+    ref = U.oracle_attention(batch, bits_from_bf16_tensor(it.q), U.oracle_kv_values(batch, kv_bits, ks, vs),
+                             it.sm_scale)
+    rep = U.error_report(batch, bits_from_bf16_tensor(it.out), ref)
+    print(batch.name, rep)
+    return rep
+
+
+def test_config1_tiny():
+    rep = run_batch(W.draw_batch(1))
+    U.assert_within_tolerance(rep)
+
+
+RAGGED = [
+    # (Hq, Hkv, D, prefix_lens, chunk_lens)
+    (8, 2, 64, [0, 3, 17, 100, 31], [1, 5, 33, 70, 129]),
+    (32, 8, 128, [0, 0, 15, 16, 255, 1000], [1, 130, 1, 17, 64, 3]),
+    (4, 4, 128, [5, 0, 63], [40, 200, 1]),          # MHA (G = 1)
+    (16, 2, 128, [77, 300], [9, 1]),                 # G = 8
+    (28, 4, 128, [10, 129, 0], [50, 1, 260]),        # G = 7 (Qwen2-7B-like grouping)
+    (8, 8, 64, [0], [1]),                            # a single key
+]
+
+
+@pytest.mark.parametrize("case", range(len(RAGGED)))
+def test_ragged_small_batches(case):
+    Hq, Hkv, D, P, C = RAGGED[case]
+    batch = W.custom_batch(W.HeadShape(Hq, Hkv, D), P, C, seed=4200 + case)
+    U.assert_within_tolerance(run_batch(batch))
+
+
+def test_long_decode_is_split_and_merged():
+    batch = W.custom_batch(W.SHAPE_8B, [8191, 4097, 700, 12000], [1, 1, 1, 1], seed=4300)
+    it = DeviceIteration(batch)
+    stats = B.cronus_attn_mixed_plan_stats(it.cache, batch.prefix_lens, batch.chunk_lens)
+    assert stats["partials"] > 0
+    U.assert_within_tolerance(run_batch(batch))
+
+
+def test_config2_scaled_down():
+    U.assert_within_tolerance(run_batch(W.draw_batch(2, scale=0.25)))
+
+
+def test_fp8_cache_small():
+    batch = W.custom_batch(W.HeadShape(16, 2, 128, "fp8"), [40, 0, 500, 1300], [90, 33, 1, 1], seed=4400)
+    U.assert_within_tolerance(run_batch(batch))
+    # power-of-two scales
+    ks = np.full(2, 2.0 ** -9, dtype=np.float32)
+    vs = np.full(2, 2.0 ** -10, dtype=np.float32)
+    U.assert_within_tolerance(run_batch(batch, scales=(ks, vs)))
+
+
+@pytest.mark.parametrize("kind", ["peaky", "outlier", "monotone", "equal"])
+def test_stress_distributions(kind):
+    shape = W.HeadShape(8, 2, 128)
+    P, C = 150, 100
+    batch = W.custom_batch(shape, [P, P + C - 1], [C, 1], seed=4500)
+    qb, kb, vb = W.stress_qkv(kind, 4500, C, P + C, shape)
+    it = DeviceIteration(batch, pool_fill=0x7FC1)
+    it.load_host_inputs()
+    from paper_2509_17357_amd.runtime import bf16_tensor_from_bits
+    # both sequences share the same K/V; the decode row is the chunk's last row
+    it.prefix_k = bf16_tensor_from_bits(np.concatenate([kb[:P], kb[:P + C - 1]]), it.device)
+    it.prefix_v = bf16_tensor_from_bits(np.concatenate([vb[:P], vb[:P + C - 1]]), it.device)
+    it.new_k = bf16_tensor_from_bits(np.concatenate([kb[P:], kb[P + C - 1:]]), it.device)
+    it.new_v = bf16_tensor_from_bits(np.concatenate([vb[P:], vb[P + C - 1:]]), it.device)
+    it.q = bf16_tensor_from_bits(np.concatenate([qb, qb[C - 1:]]), it.device)
+    it.step()
+    torch.cuda.synchronize()
+    import oracle.cronus_oracle as orc
+    q, k, v = (orc.bf16_bits_to_f64(x) for x in (qb, kb, vb))
+    ref = np.concatenate([orc.attn_rows(q, k, v, P, it.sm_scale), orc.attn_rows(q[C - 1:], k, v, P + C - 1, it.sm_scale)])
+    rep = U.error_report(batch, bits_from_bf16_tensor(it.out), ref)
+    print(kind, rep)
+    U.assert_within_tolerance(rep)
+    got = bits_from_bf16_tensor(it.out)
+    # decode == chunk of one: same keys, same query -> rows agree to bf16 rounding of different summation orders
+    d = np.abs(orc.bf16_bits_to_f64(got[C - 1]) - orc.bf16_bits_to_f64(got[C]))
+    assert d.max() <= 2e-2
+
+
+def test_error_codes():
+    batch = W.draw_batch(1)
+    it = DeviceIteration(batch)
+    it.load_host_inputs()
+    it.ensure_workspace()
+    c = it.cache
+    args = (it.q, it.out, batch.prefix_lens, batch.chunk_lens, it.block_tables, batch.max_blocks, it.sm_scale)
+    assert B.cronus_attn_mixed(c, *args, it.workspace, 16, check=False) == B.CRONUS_ERR_WORKSPACE
+    assert B.cronus_attn_mixed(c, *args, None, 1 << 20, check=False) == B.CRONUS_ERR_WORKSPACE
+    assert B.cronus_attn_mixed(c, None, it.out, *args[2:], it.workspace, it.workspace_bytes,
+                               check=False) == B.CRONUS_ERR_INVALID_ARG
+    too_long = batch.prefix_lens.copy()
+    too_long[0] = 16 * batch.max_blocks
+    assert B.cronus_attn_mixed(c, it.q, it.out, too_long, *args[3:], it.workspace, it.workspace_bytes,
+                               check=False) == B.CRONUS_ERR_INVALID_ARG
+    bad = B.make_cache(it.k_pool, it.v_pool, batch.num_blocks, 8, 2, 96)
+    assert B.cronus_attn_mixed(bad, *args, it.workspace, it.workspace_bytes, check=False) == B.CRONUS_ERR_UNSUPPORTED
+    assert B.cronus_kv_append(bad, it.new_k, it.new_v, it.cu_new, it.prefix_pos, it.block_tables, batch.max_blocks,
+                              batch.n_seqs, it.n_new_tokens, check=False) == B.CRONUS_ERR_UNSUPPORTED
+    assert B.cronus_kv_append(c, None, it.new_v, it.cu_new, it.prefix_pos, it.block_tables, batch.max_blocks,
+                              batch.n_seqs, it.n_new_tokens, check=False) == B.CRONUS_ERR_INVALID_ARG
+    # empty batch and zero-length chunks are no-ops
+    assert B.cronus_attn_mixed(c, it.q, it.out, batch.prefix_lens, np.zeros_like(batch.chunk_lens), it.block_tables,
+                               batch.max_blocks, it.sm_scale, it.workspace, it.workspace_bytes) == B.CRONUS_OK
+    torch.cuda.synchronize()
