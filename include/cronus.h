@@ -142,6 +142,16 @@ size_t cronus_attn_mixed_workspace_bytes(const cronus_kv_cache* cache, const int
 int cronus_attn_mixed_plan_stats(const cronus_kv_cache* cache, const int32_t* prefix_lens,
                                  const int32_t* chunk_lens, int32_t n_seqs, int64_t* stats);
 
+/*
+ * cronus_profile_events - measurement aid.  While both handles (hipEvent_t cast to
+ * void*, created by the caller with timing enabled) are set, every cronus_attn_mixed
+ * records `start` immediately before and `stop` immediately after its main attention
+ * kernel, on that call's stream; hipEventElapsedTime(start, stop) is then the duration
+ * of that one kernel launch.  Pass NULL, NULL to switch it off (the default).
+ * Process-wide; not meant for concurrent callers.
+ */
+void cronus_profile_events(void* start_event, void* stop_event);
+
 /* Static, NUL-terminated description of a cronus_status. */
 const char* cronus_status_string(int status);
 

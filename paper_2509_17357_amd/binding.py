@@ -24,7 +24,7 @@ CRONUS_KV_BF16 = 0
 CRONUS_KV_FP8_E4M3 = 1
 
 EXPORTS = ("cronus_kv_append", "cronus_attn_mixed", "cronus_attn_mixed_workspace_bytes",
-           "cronus_attn_mixed_plan_stats", "cronus_status_string", "cronus_version")
+           "cronus_attn_mixed_plan_stats", "cronus_profile_events", "cronus_status_string", "cronus_version")
 
 
 class cronus_kv_cache(ctypes.Structure):
@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.cronus_attn_mixed_workspace_bytes.restype = ctypes.c_size_t
         L.cronus_attn_mixed_plan_stats.argtypes = [cp, i32p, i32p, i32, ctypes.POINTER(ctypes.c_int64)]
         L.cronus_attn_mixed_plan_stats.restype = ctypes.c_int
+        L.cronus_profile_events.argtypes = [vp, vp]
+        L.cronus_profile_events.restype = None
         L.cronus_status_string.argtypes = [ctypes.c_int]
         L.cronus_status_string.restype = ctypes.c_char_p
         L.cronus_version.argtypes = []
@@ -77,6 +79,39 @@ def status_string(status: int) -> str:
 
 def version() -> int:
     return lib().cronus_version()
+
+
+def cronus_profile_events(start_event: int | None, stop_event: int | None) -> None:
+    lib().cronus_profile_events(ctypes.c_void_p(start_event), ctypes.c_void_p(stop_event))
+
+
+class HipEvents:
+    """Plain hipEvent_t handles (timing enabled) for cronus_profile_events."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+
+    def create(self) -> int:
+        ev = ctypes.c_void_p()
+        rc = self.hip.hipEventCreate(ctypes.byref(ev))
+        if rc != 0:
+            raise RuntimeError(f"hipEventCreate failed ({rc})")
+        return ev.value
+
+    def elapsed_ms(self, start: int, stop: int) -> float:
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventSynchronize(stop)
+        rc = rc or self.hip.hipEventElapsedTime(ctypes.byref(ms), start, stop)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed ({rc})")
+        return float(ms.value)
+
+    def destroy(self, ev: int) -> None:
+        self.hip.hipEventDestroy(ev)
 
 
 def _ptr(t):

@@ -57,6 +57,9 @@ struct Slot {
   hipEvent_t done = nullptr;
   bool pending = false;
 };
+void* g_ev_start = nullptr;
+void* g_ev_stop = nullptr;
+
 constexpr int kSlots = 8;
 Slot g_slots[kSlots];
 int g_next = 0;
@@ -157,8 +160,14 @@ int cronus_attn_mixed(const cronus_kv_cache* cache, const void* q, void* out, co
     if (hipEventRecord(slot->done, stream) != hipSuccess) return CRONUS_ERR_HIP;
     slot->pending = true;
   }
-  AttnLaunch a{cache, q, out, block_tables, max_blocks_per_seq, sm_scale, workspace, &plan, hip_stream};
+  AttnLaunch a{cache, q, out, block_tables, max_blocks_per_seq, sm_scale, workspace, &plan, hip_stream,
+               g_ev_start, g_ev_stop};
   return launch_attn(a);
+}
+
+void cronus_profile_events(void* start_event, void* stop_event) {
+  g_ev_start = start_event;
+  g_ev_stop = stop_event;
 }
 
 const char* cronus_status_string(int status) {

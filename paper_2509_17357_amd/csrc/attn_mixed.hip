@@ -556,8 +556,11 @@ int launch_typed(const AttnLaunch& a, const AttnParams& p) {
         return CRONUS_ERR_HIP;
       attr_set = true;
     }
+    const bool timed = a.ev_start && a.ev_stop;
+    if (timed && hipEventRecord(static_cast<hipEvent_t>(a.ev_start), s) != hipSuccess) return CRONUS_ERR_HIP;
     hipLaunchKernelGGL(kern, dim3((unsigned)pl.n_items), dim3(kThreads), lds, s, p);
     if (hipGetLastError() != hipSuccess) return CRONUS_ERR_HIP;
+    if (timed && hipEventRecord(static_cast<hipEvent_t>(a.ev_stop), s) != hipSuccess) return CRONUS_ERR_HIP;
   }
   if (pl.n_merge > 0) {
     hipLaunchKernelGGL((attn_merge_kernel<D, FP8>), dim3((unsigned)pl.n_merge), dim3(D), 0, s, p);

@@ -82,6 +82,8 @@ struct AttnLaunch {
   void* workspace;  // device; metadata already uploaded
   const Plan* plan;
   void* stream;
+  void* ev_start;  // optional hipEvent_t pair recorded around the main kernel
+  void* ev_stop;
 };
 
 int launch_attn(const AttnLaunch& a);

@@ -2,9 +2,12 @@
 every computation through the C ABI (binding.py).  No oracle, no fallback.
 
 The hot path of one iteration (Cronus section 4.2 and 4.4) is, in order:
-  1. ingest_prefix  - cronus_kv_append of the transferred prefix KV (start_pos = 0)
+  1. ingest_prefix  - cronus_kv_append of the transferred prefix KV of the continuation
+                      chunks (start_pos = 0)
   2. append_new     - cronus_kv_append of this iteration's K/V rows (start_pos = prefix)
   3. attention      - cronus_attn_mixed over chunks and decodes
+The contexts of the decode requests were cached by earlier iterations; here they are
+placed by setup_decode_context(), which is set-up, not part of the iteration.
 """
 from __future__ import annotations
 
@@ -47,11 +50,15 @@ class DeviceIteration:
         self.prefix_k = self.prefix_v = self.new_k = self.new_v = None
         P, C = batch.prefix_lens.astype(np.int64), batch.chunk_lens.astype(np.int64)
         i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(self.device)
-        self.cu_prefix = i32(np.concatenate([[0], np.cumsum(P)]))
+        is_dec = C == 1
+        self.cu_prefix = i32(np.concatenate([[0], np.cumsum(np.where(is_dec, 0, P))]))  # chunk sequences only
+        self.cu_ctx = i32(np.concatenate([[0], np.cumsum(np.where(is_dec, P, 0))]))     # decode sequences only
+        self.n_ctx_tokens = int(P[is_dec].sum())
+        self.ctx_k = self.ctx_v = None
         self.cu_new = i32(np.concatenate([[0], np.cumsum(C)]))
         self.zero_pos = i32(np.zeros(batch.n_seqs))
         self.prefix_pos = i32(P)
-        self.n_prefix_tokens = int(P.sum())
+        self.n_prefix_tokens = int(P[~is_dec].sum())
         self.n_new_tokens = int(C.sum())
         self.sm_scale = 1.0 / float(np.sqrt(sh.head_dim))
         self._cache = None
@@ -68,8 +75,11 @@ class DeviceIteration:
         sh = b.shape
         empty = np.zeros((0, sh.n_kv_heads, sh.head_dim), dtype=np.uint16)
         cat = lambda xs: np.concatenate(xs) if xs else empty
-        self.prefix_k = bf16_tensor_from_bits(cat([k[:P[s]] for s, (k, v) in enumerate(kv)]), self.device)
-        self.prefix_v = bf16_tensor_from_bits(cat([v[:P[s]] for s, (k, v) in enumerate(kv)]), self.device)
+        dec = b.chunk_lens == 1
+        self.prefix_k = bf16_tensor_from_bits(cat([k[:P[s]] for s, (k, v) in enumerate(kv) if not dec[s]]), self.device)
+        self.prefix_v = bf16_tensor_from_bits(cat([v[:P[s]] for s, (k, v) in enumerate(kv) if not dec[s]]), self.device)
+        self.ctx_k = bf16_tensor_from_bits(cat([k[:P[s]] for s, (k, v) in enumerate(kv) if dec[s]]), self.device)
+        self.ctx_v = bf16_tensor_from_bits(cat([v[:P[s]] for s, (k, v) in enumerate(kv) if dec[s]]), self.device)
         self.new_k = bf16_tensor_from_bits(cat([k[P[s]:] for s, (k, v) in enumerate(kv)]), self.device)
         self.new_v = bf16_tensor_from_bits(cat([v[P[s]:] for s, (k, v) in enumerate(kv)]), self.device)
         self.q = bf16_tensor_from_bits(b.gen_q(), self.device)
@@ -84,6 +94,7 @@ class DeviceIteration:
         mk = lambda n: (torch.randn((n, sh.n_kv_heads, sh.head_dim), generator=g, device=self.device,
                                     dtype=torch.float32) * 0.125).to(torch.bfloat16)
         self.prefix_k, self.prefix_v = mk(self.n_prefix_tokens), mk(self.n_prefix_tokens)
+        self.ctx_k, self.ctx_v = mk(self.n_ctx_tokens), mk(self.n_ctx_tokens)
         self.new_k, self.new_v = mk(self.n_new_tokens), mk(self.n_new_tokens)
         self.q = (torch.randn((self.n_new_tokens, sh.n_q_heads, sh.head_dim), generator=g, device=self.device,
                               dtype=torch.float32) * 0.125).to(torch.bfloat16)
@@ -96,10 +107,10 @@ class DeviceIteration:
 
     def amax_scales(self):
         """Per-KV-head scale = amax / 448 in fp32 over the tensors about to be cached."""
-        def amax(a, b):
-            x = torch.cat([a, b]).abs().amax(dim=(0, 2)).to(torch.float32)
-            return (x / 448.0).cpu().numpy().astype(np.float32)
-        return amax(self.prefix_k, self.new_k), amax(self.prefix_v, self.new_v)
+        def amax(a, b, c):
+            x = torch.cat([t.abs().amax(dim=(0, 2))[None] for t in (a, b, c) if t.shape[0]]).amax(dim=0)
+            return (x.to(torch.float32) / 448.0).cpu().numpy().astype(np.float32)
+        return amax(self.prefix_k, self.new_k, self.ctx_k), amax(self.prefix_v, self.new_v, self.ctx_v)
 
     # ---- the C ABI calls
     @property
@@ -114,12 +125,17 @@ class DeviceIteration:
     def _stream(self):
         return torch.cuda.current_stream(self.device).cuda_stream
 
-    def ingest_prefix(self, only_seqs=None):
+    def setup_decode_context(self):
+        """Set-up: the KV that earlier iterations of the decode requests left in the cache."""
         b = self.batch
-        if only_seqs is None:
-            return B.cronus_kv_append(self.cache, self.prefix_k, self.prefix_v, self.cu_prefix, self.zero_pos,
-                                      self.block_tables, b.max_blocks, b.n_seqs, self.n_prefix_tokens, self._stream())
-        raise NotImplementedError
+        return B.cronus_kv_append(self.cache, self.ctx_k, self.ctx_v, self.cu_ctx, self.zero_pos,
+                                  self.block_tables, b.max_blocks, b.n_seqs, self.n_ctx_tokens, self._stream())
+
+    def ingest_prefix(self):
+        """Hot path: the transferred prefix of every continuation chunk."""
+        b = self.batch
+        return B.cronus_kv_append(self.cache, self.prefix_k, self.prefix_v, self.cu_prefix, self.zero_pos,
+                                  self.block_tables, b.max_blocks, b.n_seqs, self.n_prefix_tokens, self._stream())
 
     def append_new(self):
         b = self.batch
@@ -142,7 +158,7 @@ class DeviceIteration:
                                    b.max_blocks, self.sm_scale, self.workspace, self.workspace_bytes, self._stream())
 
     def step(self):
-        """One pass of the whole hot path."""
+        """One pass of the whole hot path (after setup_decode_context())."""
         self.ingest_prefix()
         self.append_new()
         self.attention()

@@ -23,6 +23,7 @@ def run_batch(batch, poison=True, check_pools=True, scales=None):
     if it.fp8:
         ks, vs = scales if scales is not None else it.amax_scales()
         it.set_fp8_scales(ks, vs)
+    it.setup_decode_context()
     it.step()
     torch.cuda.synchronize()
     if check_pools:
@@ -91,11 +92,12 @@ def test_stress_distributions(kind):
     it.load_host_inputs()
     from paper_2509_17357_amd.runtime import bf16_tensor_from_bits
     # both sequences share the same K/V; the decode row is the chunk's last row
-    it.prefix_k = bf16_tensor_from_bits(np.concatenate([kb[:P], kb[:P + C - 1]]), it.device)
-    it.prefix_v = bf16_tensor_from_bits(np.concatenate([vb[:P], vb[:P + C - 1]]), it.device)
+    it.prefix_k, it.ctx_k = bf16_tensor_from_bits(kb[:P], it.device), bf16_tensor_from_bits(kb[:P + C - 1], it.device)
+    it.prefix_v, it.ctx_v = bf16_tensor_from_bits(vb[:P], it.device), bf16_tensor_from_bits(vb[:P + C - 1], it.device)
     it.new_k = bf16_tensor_from_bits(np.concatenate([kb[P:], kb[P + C - 1:]]), it.device)
     it.new_v = bf16_tensor_from_bits(np.concatenate([vb[P:], vb[P + C - 1:]]), it.device)
     it.q = bf16_tensor_from_bits(np.concatenate([qb, qb[C - 1:]]), it.device)
+    it.setup_decode_context()
     it.step()
     torch.cuda.synchronize()
     import oracle.cronus_oracle as orc
