@@ -20,7 +20,7 @@
 #include "cronus_internal.h"
 
 #ifndef CRONUS_WIDE_QT
-#define CRONUS_WIDE_QT 2
+#define CRONUS_WIDE_QT 1
 #endif
 
 namespace cronus {
@@ -225,20 +225,22 @@ __device__ __forceinline__ void run_wide(const AttnParams& p, const WorkItem& it
   const int n_tiles = (it.kv_end - it.kv_begin + kWideKvTile - 1) / kWideKvTile;
 
   Raw rk[PER], rv[PER];
+  int bt_next[PER];  // physical blocks of the tile that will be fetched next (looked up one tile early)
+  auto lookup_blocks = [&](int tile_base) {
+#pragma unroll
+    for (int n = 0; n < PER; ++n) {
+      const int bidx = (tile_base >> 4) + (tid + kThreads * n) / CH_PER_BLK;
+      bt_next[n] = bt[min(bidx, si.n_blocks - 1)];
+    }
+  };
   auto stage_load = [&](int tile_base) {
 #pragma unroll
     for (int n = 0; n < PER; ++n) {
       const int id = tid + kThreads * n;
-      const int blk = id / CH_PER_BLK, off = id - blk * CH_PER_BLK;
-      const int bidx = (tile_base >> 4) + blk;
-      if (bidx < si.n_blocks) {
-        const long long base = ((long long)bt[bidx] * p.n_kv_heads + it.kv_head) * head_stride + (long long)off * 8 * ESZ;
-        rk[n] = load_chunk<FP8>(p.k_pool + base);
-        rv[n] = load_chunk<FP8>(p.v_pool + base);
-      } else {
-        rk[n] = Raw(0);
-        rv[n] = Raw(0);
-      }
+      const int off = id % CH_PER_BLK;
+      const long long base = ((long long)bt_next[n] * p.n_kv_heads + it.kv_head) * head_stride + (long long)off * 8 * ESZ;
+      rk[n] = load_chunk<FP8>(p.k_pool + base);
+      rv[n] = load_chunk<FP8>(p.v_pool + base);
     }
   };
   auto stage_store = [&](int buf, int tile_base) {
@@ -264,13 +266,18 @@ __device__ __forceinline__ void run_wide(const AttnParams& p, const WorkItem& it
   const int k_lane_off = (pr >> 4) * BLK_LDS + (half * 16 + (pr & 15)) * 16;
   const int v_lane_off = (half * D + pr) * 16;
 
+  lookup_blocks(it.kv_begin);
   stage_load(it.kv_begin);
+  lookup_blocks(it.kv_begin + kWideKvTile);
   int buf = 0;
   for (int j = 0; j < n_tiles; ++j) {
     const int tile_base = it.kv_begin + j * kWideKvTile;
     stage_store(buf, tile_base);
     __syncthreads();
-    if (j + 1 < n_tiles) stage_load(tile_base + kWideKvTile);
+    if (j + 1 < n_tiles) {
+      stage_load(tile_base + kWideKvTile);
+      lookup_blocks(tile_base + 2 * kWideKvTile);
+    }
     if (wave_active && tile_base <= wave_max_limit) {
       const unsigned char* kb = smem + buf * STAGE;
       const unsigned char* vb = kb + KT_BYTES;
@@ -333,11 +340,50 @@ struct NarrowOps {
   typename RawChunk<FP8>::type v[2 * (D / 32)];
 };
 
+typedef __attribute__((address_space(3))) unsigned char lds_byte;
+
+// LDS reads of data that arrived by global_load_lds.  They are written as asm so that
+// the waits on those loads are the explicit s_waitcnt below and nothing coarser.
+#define CRONUS_LDS_READ128(dst, addr, OFF) \
+  asm volatile("ds_read_b128 %0, %1 offset:" #OFF : "=v"(dst) : "v"(addr) : "memory")
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N == 0 || N == 4 || N == 8, "counts used by the narrow pipeline");
+  if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+  if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+}
+
+// Read the NOPS 1-KiB operand planes of this lane (plane n at addr + 1024 n) and wait
+// for them; the "+v" operands tie the wait to the registers the MFMAs consume.
+template <int NOPS>
+__device__ __forceinline__ void lds_read_planes(u32x4 (&x)[NOPS], unsigned addr) {
+  static_assert(NOPS == 4 || NOPS == 8, "D = 64 or 128");
+  CRONUS_LDS_READ128(x[0], addr, 0);
+  CRONUS_LDS_READ128(x[1], addr, 1024);
+  CRONUS_LDS_READ128(x[2], addr, 2048);
+  CRONUS_LDS_READ128(x[3], addr, 3072);
+  if constexpr (NOPS == 8) {
+    CRONUS_LDS_READ128(x[4], addr, 4096);
+    CRONUS_LDS_READ128(x[5], addr, 5120);
+    CRONUS_LDS_READ128(x[6], addr, 6144);
+    CRONUS_LDS_READ128(x[7], addr, 7168);
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7])
+                 :
+                 : "memory");
+  } else {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]) : : "memory");
+  }
+}
+
 template <int D, bool FP8>
 __device__ __forceinline__ void run_narrow(const AttnParams& p, const WorkItem& it, unsigned char* smem) {
   constexpr int NSTEP = D / 16, NDB = D / 32;
   constexpr int ESZ = FP8 ? 1 : 2;
   constexpr int NACC = NDB * 16;
+  constexpr int WAVE_LDS = 2 * NSTEP * 1024;  // per-wave LDS: K planes then V planes (= NACC * 256)
   using Raw = typename RawChunk<FP8>::type;
 
   const int tid = threadIdx.x;
@@ -359,7 +405,13 @@ __device__ __forceinline__ void run_narrow(const AttnParams& p, const WorkItem& 
     const unsigned short* qp =
         p.q + ((long long)(si.q_off + it.q_tok0 + t_row) * p.n_q_heads + it.head0 + gi_row) * D + 8 * half;
 #pragma unroll
-    for (int s = 0; s < NSTEP; ++s) qreg[s] = as_bf16x8(*reinterpret_cast<const u32x4*>(qp + 16 * s));
+    for (int s = 0; s < NSTEP; ++s) {
+      u32x4 qv = *reinterpret_cast<const u32x4*>(qp + 16 * s);
+      // pin the wait for this load here: inside the streaming loop it would have to
+      // be a wait for every load in flight
+      asm volatile("" : "+v"(qv));
+      qreg[s] = as_bf16x8(qv);
+    }
   }
 
   f32x16 o[NDB];
@@ -372,91 +424,153 @@ __device__ __forceinline__ void run_narrow(const AttnParams& p, const WorkItem& 
   const int* bt = p.block_tables + (long long)it.seq * p.max_blocks;
   const long long head_stride = (long long)16 * D * ESZ;
   const int n_sub = (it.kv_end - it.kv_begin + 31) >> 5;
+  const int last_blk = si.n_blocks - 1;
   const int pr = perm32(c32);
   const long long k_lane_off = (long long)(half * 16 + (pr & 15)) * 8 * ESZ;
   const long long v_lane_off = (long long)(half * D + pr) * 8 * ESZ;
 
-  auto load_ops = [&](NarrowOps<D, FP8>& ops, int u) {
-    if (u >= n_sub) return;
-    const int blk0 = (it.kv_begin + 32 * u) >> 4;
-    const int kb = blk0 + (pr >> 4);
-    if (kb < si.n_blocks) {
-      const unsigned char* kp = p.k_pool + ((long long)bt[kb] * p.n_kv_heads + it.kv_head) * head_stride + k_lane_off;
-#pragma unroll
-      for (int s = 0; s < NSTEP; ++s) ops.k[s] = load_chunk<FP8>(kp + s * (256 * ESZ));
-    } else {
-#pragma unroll
-      for (int s = 0; s < NSTEP; ++s) ops.k[s] = Raw(0);
-    }
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      if (blk0 + t < si.n_blocks) {
-        const unsigned char* vp =
-            p.v_pool + ((long long)bt[blk0 + t] * p.n_kv_heads + it.kv_head) * head_stride + v_lane_off;
-#pragma unroll
-        for (int db = 0; db < NDB; ++db) ops.v[t * NDB + db] = load_chunk<FP8>(vp + db * (256 * ESZ));
-      } else {
-#pragma unroll
-        for (int db = 0; db < NDB; ++db) ops.v[t * NDB + db] = Raw(0);
-      }
-    }
-  };
-
-  auto process = [&](const NarrowOps<D, FP8>& ops, int u) {
-    const int sub_base = it.kv_begin + 32 * u;
-    f32x16 s;
+  auto compute_s = [&](const u32x4 (&kop)[NSTEP], f32x16& s) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) s[i] = 0.f;
 #pragma unroll
     for (int st = 0; st < NSTEP; ++st)
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(to_bf16_chunk<FP8>(ops.k[st])), qreg[st], s, 0, 0, 0);
-    u32x4 pp[2];
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kop[st]), qreg[st], s, 0, 0, 0);
+  };
+  auto softmax = [&](f32x16& s, u32x4 (&pp)[2], int u) {
+    const int sub_base = it.kv_begin + 32 * u;
     softmax_tile<NDB>(s, sub_base + 31 > min_limit, sub_base, half, limit, c, m, l, o, pp);
-    const bool tail = sub_base + 32 > kv_len;
+  };
+  auto compute_pv = [&](u32x4 (&vop)[NSTEP], const u32x4 (&pp)[2], int u) {
+    const int sub_base = it.kv_begin + 32 * u;
+    if (sub_base + 32 > kv_len) {  // last sub-tile of the sequence: slots past its length hold anything
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+          vop[t * NDB + db] = zero_tail(vop[t * NDB + db], sub_base + 16 * t + 8 * half, kv_len);
+    }
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int db = 0; db < NDB; ++db) {
-        u32x4 vv = to_bf16_chunk<FP8>(ops.v[t * NDB + db]);
-        if (tail) vv = zero_tail(vv, sub_base + 16 * t + 8 * half, kv_len);
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vv), as_bf16x8(pp[t]), o[db], 0, 0, 0);
-      }
+      for (int db = 0; db < NDB; ++db)
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vop[t * NDB + db]), as_bf16x8(pp[t]), o[db], 0, 0, 0);
   };
 
-  // three operand sets in flight per wave: wave w takes sub-tiles w, w+4, w+8, ...
-  NarrowOps<D, FP8> a, b, cc;
-  load_ops(a, wave);
-  load_ops(b, wave + kWaves);
-  for (int u = wave; u < n_sub; u += 3 * kWaves) {
-    load_ops(cc, u + 2 * kWaves);
-    process(a, u);
-    if (u + kWaves < n_sub) {
-      load_ops(a, u + 3 * kWaves);
-      process(b, u + kWaves);
+  if constexpr (!FP8) {
+    // K/V chunks go global -> LDS by DMA, one 16-byte chunk per lane per instruction, into
+    // this wave's private planes; each lane later reads back exactly the chunk it fetched,
+    // so LDS only serves as storage for loads in flight (no registers are tied up).
+    lds_byte* wl = (lds_byte*)smem + wave * WAVE_LDS;
+    const unsigned rd_addr = (unsigned)(unsigned long long)wl + lane * 16;  // LDS byte address
+    // Block-table entries of this wave's next 32 sub-tiles live in one register (two
+    // lanes per sub-tile) and are picked with readlane: a table load inside the loop
+    // would have to wait behind every DMA load in flight.
+    int bt_reg = 0;
+    auto load_table = [&](int j0) {
+      const int uu = wave + kWaves * (j0 + (lane >> 1));
+      bt_reg = bt[min(((it.kv_begin + 32 * uu) >> 4) + (lane & 1), last_blk)];
+      asm volatile("" : "+v"(bt_reg));  // wait for it here, not at each use
+    };
+    auto issue_k = [&](int j) {
+      const long long b0 = __builtin_amdgcn_readlane(bt_reg, 2 * (j & 31));
+      const long long b1 = __builtin_amdgcn_readlane(bt_reg, 2 * (j & 31) + 1);
+      const unsigned char* g =
+          p.k_pool + (((pr >> 4) ? b1 : b0) * p.n_kv_heads + it.kv_head) * head_stride + k_lane_off;
+#pragma unroll
+      for (int st = 0; st < NSTEP; ++st) __builtin_amdgcn_global_load_lds(g + st * 512, wl + st * 1024, 16, 0, 0);
+    };
+    auto issue_v = [&](int j) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const long long b = __builtin_amdgcn_readlane(bt_reg, 2 * (j & 31) + t);
+        const unsigned char* g = p.v_pool + (b * p.n_kv_heads + it.kv_head) * head_stride + v_lane_off;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+          __builtin_amdgcn_global_load_lds(g + db * 512, wl + (NSTEP + t * NDB + db) * 1024, 16, 0, 0);
+      }
+    };
+    const int n_iter = n_sub > wave ? (n_sub - wave + kWaves - 1) / kWaves : 0;  // sub-tiles wave, wave+4, ...
+    if (n_iter > 0) {
+      load_table(0);
+      issue_k(0);
+      issue_v(0);
     }
-    if (u + 2 * kWaves < n_sub) {
-      load_ops(b, u + 4 * kWaves);
-      process(cc, u + 2 * kWaves);
+    for (int j = 0; j < n_iter; ++j) {
+      const int u = wave + kWaves * j;
+      const bool has_next = j + 1 < n_iter;
+      u32x4 kop[NSTEP], vop[NSTEP], pp[2];
+      f32x16 s;
+      wait_vmcnt<NSTEP>();  // K(j) landed; the V(j) loads issued after it may still fly
+      lds_read_planes<NSTEP>(kop, rd_addr);
+      compute_s(kop, s);
+      if (has_next) {
+        if (((j + 1) & 31) == 0) load_table(j + 1);
+        issue_k(j + 1);  // the K planes are free again
+      }
+      softmax(s, pp, u);
+      if (has_next) wait_vmcnt<NSTEP>(); else wait_vmcnt<0>();  // V(j) landed
+      lds_read_planes<NSTEP>(vop, rd_addr + NSTEP * 1024);
+      compute_pv(vop, pp, u);
+      if (has_next) issue_v(j + 1);
+    }
+  } else {
+    // fp8: chunks are 8 bytes; two operand sets in registers, converted when consumed
+    auto load_ops = [&](NarrowOps<D, FP8>& ops, int u) {
+      if (u >= n_sub) return;
+      const int blk0 = (it.kv_begin + 32 * u) >> 4;
+      const unsigned char* kp =
+          p.k_pool + ((long long)bt[min(blk0 + (pr >> 4), last_blk)] * p.n_kv_heads + it.kv_head) * head_stride + k_lane_off;
+#pragma unroll
+      for (int s = 0; s < NSTEP; ++s) ops.k[s] = load_chunk<FP8>(kp + s * (256 * ESZ));
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const unsigned char* vp =
+            p.v_pool + ((long long)bt[min(blk0 + t, last_blk)] * p.n_kv_heads + it.kv_head) * head_stride + v_lane_off;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) ops.v[t * NDB + db] = load_chunk<FP8>(vp + db * (256 * ESZ));
+      }
+    };
+    auto consume = [&](const NarrowOps<D, FP8>& ops, int u) {
+      u32x4 kop[NSTEP], vop[NSTEP], pp[2];
+      f32x16 s;
+#pragma unroll
+      for (int i = 0; i < NSTEP; ++i) kop[i] = to_bf16_chunk<FP8>(ops.k[i]);
+      compute_s(kop, s);
+      softmax(s, pp, u);
+#pragma unroll
+      for (int i = 0; i < NSTEP; ++i) vop[i] = to_bf16_chunk<FP8>(ops.v[i]);
+      compute_pv(vop, pp, u);
+    };
+    NarrowOps<D, FP8> a, b;
+    load_ops(a, wave);
+    for (int u = wave; u < n_sub; u += 2 * kWaves) {
+      load_ops(b, u + kWaves);
+      consume(a, u);
+      if (u + kWaves < n_sub) {
+        load_ops(a, u + 2 * kWaves);
+        consume(b, u + kWaves);
+      }
     }
   }
 
-  // combine the four waves (each covered different keys) in wave 0
-  float* xch = reinterpret_cast<float*>(smem);  // [3][NACC + 2][64]
+  // combine the four waves (each covered different keys) in wave 0: every wave parks its
+  // accumulators in its own LDS planes (its reads of them are complete)
+  float* xo = reinterpret_cast<float*>(smem + wave * WAVE_LDS) + lane;        // [NACC][64]
+  float* xs = reinterpret_cast<float*>(smem + kWaves * WAVE_LDS) + lane;      // [kWaves][2][64]
   if (wave > 0) {
-    float* w = xch + (wave - 1) * (NACC + 2) * 64 + lane;
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) w[(db * 16 + i) * 64] = o[db][i];
-    w[NACC * 64] = m;
-    w[(NACC + 1) * 64] = l;
+      for (int i = 0; i < 16; ++i) xo[(db * 16 + i) * 64] = o[db][i];
+    xs[(wave * 2) * 64] = m;
+    xs[(wave * 2 + 1) * 64] = l;
   }
   __syncthreads();
   if (wave == 0) {
 #pragma unroll 1
-    for (int w2 = 0; w2 < kWaves - 1; ++w2) {
-      const float* w = xch + w2 * (NACC + 2) * 64 + lane;
-      const float mo = w[NACC * 64], lo = w[(NACC + 1) * 64];
+    for (int w2 = 1; w2 < kWaves; ++w2) {
+      const float* w = reinterpret_cast<const float*>(smem + w2 * WAVE_LDS) + lane;
+      const float mo = xs[(w2 * 2) * 64], lo = xs[(w2 * 2 + 1) * 64];
       const float mn = fmaxf(m, mo);
       const float a0 = __builtin_amdgcn_exp2f((m - mn) * c), a1 = __builtin_amdgcn_exp2f((mo - mn) * c);
 #pragma unroll
@@ -467,13 +581,6 @@ __device__ __forceinline__ void run_narrow(const AttnParams& p, const WorkItem& 
       m = mn;
     }
     float lt = pair_sum(l);
-    if (m <= kNeg) {  // no visible key in this span for this row
-      lt = 0.f;
-#pragma unroll
-      for (int db = 0; db < NDB; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
-    }
     if (c32 < rows_valid) {
       if (it.partial < 0) {
         const float vmul = FP8 ? p.v_scale[it.kv_head] : 1.0f;
@@ -503,7 +610,7 @@ __device__ __forceinline__ void run_narrow(const AttnParams& p, const WorkItem& 
 }
 
 template <int D, bool FP8, int QT>
-__global__ __launch_bounds__(kThreads) void attn_mixed_kernel(AttnParams p) {
+__global__ __launch_bounds__(kThreads, 2) void attn_mixed_kernel(AttnParams p) {
   extern __shared__ __align__(16) unsigned char smem[];
   const WorkItem it = p.items[blockIdx.x];
   if (it.wide) run_wide<D, FP8, QT>(p, it, smem);
@@ -542,7 +649,7 @@ template <int D, bool FP8>
 int launch_typed(const AttnLaunch& a, const AttnParams& p) {
   constexpr int QT = CRONUS_WIDE_QT;
   constexpr int wide_lds = 2 * 2 * 4 * 16 * D * 2;
-  constexpr int narrow_lds = 3 * ((D / 32) * 16 + 2) * 64 * 4;
+  constexpr int narrow_lds = kWaves * (2 * (D / 16) * 1024) + kWaves * 2 * 64 * 4;
   constexpr int lds = wide_lds > narrow_lds ? wide_lds : narrow_lds;
   static_assert(lds <= 160 * 1024, "LDS budget");
   hipStream_t s = static_cast<hipStream_t>(a.stream);
