@@ -161,6 +161,8 @@ def main():
     ap.add_argument("--workload", default="llama3_8b", choices=sorted(WORKLOADS))
     ap.add_argument("--no-extra", action="store_true", help="skip the prefill-heavy / decode-heavy runs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain 1 GiB device copy (reference for the FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
@@ -170,6 +172,16 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(2)
+
+    if args.calibrate_copy:
+        n = 1 << 30
+        src = torch.full((n,), 7, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(max(1, args.steps)):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "launches": max(1, args.steps)}))
+        return
 
     main_res, batch = time_workload(args.workload, args.steps, args.warmup)
     others = {}

@@ -13,7 +13,7 @@ from dataclasses import dataclass
 import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libcronus.so")
+LIB_PATH = os.environ.get("CRONUS_LIB", os.path.join(HERE, "libcronus.so"))  # CRONUS_LIB: another build of the same library
 
 CRONUS_OK = 0
 CRONUS_ERR_INVALID_ARG = 1

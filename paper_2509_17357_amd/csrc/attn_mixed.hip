@@ -1,13 +1,16 @@
 // Mixed-iteration attention for gfx950 (Cronus section 4.4: one iteration of the
 // chunked prefill instance batches a continuation chunk with decodes; Eq. 3 names
 // the two attention terms).  One launch runs every work item of the batch:
-//   wide item   - a tile of chunk rows (tokens x the q heads of one KV head) against
+//   wide item   - a tile of 256 chunk rows (tokens x the q heads of one KV head) against
 //                 keys 0 .. its causal limit; K/V blocks are staged through LDS and
-//                 shared by the 4 waves, each wave owning 32*QT rows.
+//                 shared by the 8 waves, each wave owning 32 rows.  For a bf16 cache
+//                 the blocks arrive by global->LDS DMA four tiles deep and the two
+//                 waves of every SIMD alternate between an MFMA phase and a softmax
+//                 phase (ping-pong, one s_barrier per phase).
 //   narrow item - at most 32 rows (a decode, or a short chunk) against a span of
-//                 keys; the 4 waves split the span and stream K/V chunks straight
-//                 from the paged pools into MFMA operands; partial results of
-//                 spans are combined by the merge kernel.
+//                 keys; the 8 waves split the span and stream K/V chunks from the
+//                 paged pools; partial results of spans are combined by the merge
+//                 kernel.
 //
 // Both compute S^T = K Q^T and O^T = V^T P^T with v_mfma_f32_32x32x16_bf16, so a
 // lane owns one query row (column of S^T): its softmax statistics are lane-local
@@ -18,10 +21,6 @@
 #include <hip/hip_runtime.h>
 
 #include "cronus_internal.h"
-
-#ifndef CRONUS_WIDE_QT
-#define CRONUS_WIDE_QT 1
-#endif
 
 namespace cronus {
 namespace {
@@ -167,15 +166,16 @@ __device__ __forceinline__ void store_row_bf16(unsigned short* row_ptr, const f3
     }
 }
 
-// ------------------------------------------------------------------ wide (chunk) tile
+// ---------------------------------------- wide (chunk) tile, staged through registers
+// Used for the fp8 cache: codes are converted to bf16 once, on their way into LDS.
 template <int D, bool FP8, int QT>
-__device__ __forceinline__ void run_wide(const AttnParams& p, const WorkItem& it, unsigned char* smem) {
+__device__ __forceinline__ void run_wide_staged(const AttnParams& p, const WorkItem& it, unsigned char* smem) {
   constexpr int NSTEP = D / 16, NDB = D / 32;
   constexpr int BLK_LDS = 16 * D * 2;           // bytes of one (block, head) as bf16
   constexpr int KT_BYTES = 4 * BLK_LDS;         // K (or V) tile: 64 keys
   constexpr int STAGE = 2 * KT_BYTES;
   constexpr int CH_PER_BLK = 2 * D;             // 8-element chunks per (block, head)
-  constexpr int PER = D / 32;                   // chunks of K (and of V) each thread stages
+  constexpr int PER = 8 * D / kThreads;         // chunks of K (and of V) each thread stages
   constexpr int ESZ = FP8 ? 1 : 2;
   using Raw = typename RawChunk<FP8>::type;
 
@@ -333,6 +333,226 @@ __device__ __forceinline__ void run_wide(const AttnParams& p, const WorkItem& it
   }
 }
 
+
+// ------------------------------------- wide (chunk) tile, bf16 cache: DMA-fed pipeline
+typedef __attribute__((address_space(3))) unsigned char lds_byte;
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N == 0 || N == 2 || N == 4 || N == 8, "counts used by the DMA pipelines");
+  if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  if constexpr (N == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+  if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+  if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+}
+
+// LDS reads of data that arrived by global_load_lds are written as asm: the waits on
+// those loads are then the explicit s_waitcnt of the pipeline and nothing coarser.
+template <int OFF>
+__device__ __forceinline__ void lds_read128(u32x4& dst, unsigned addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "i"(OFF) : "memory");
+}
+// Wait for every LDS read issued so far; the "+v" operands tie the wait to the
+// registers that the following MFMAs consume.
+template <int N>
+__device__ __forceinline__ void lds_wait(u32x4 (&x)[N]) {
+  static_assert(N == 4 || N == 8, "D = 64 or 128");
+  if constexpr (N == 8)
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7])
+                 :
+                 : "memory");
+  else
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]) : : "memory");
+}
+
+// Schedule per wave (n = number of 32-key sub-tiles, S(u) = K(u) Q^T, P(u) = softmax
+// numerators), software-pipelined by one sub-tile so that the MFMA pipe has the S(u+1)
+// products to work on while the VALU computes the softmax of S(u):
+//   S(0); for u = 0 .. n-1 { S(u+1) (MFMA) | read V(u) | P(u) = softmax(S(u)) (VALU) |
+//                            read K(u+2) | O += V(u)^T P(u) (MFMA) }
+// K/V tiles of 64 keys arrive by DMA into a ring of kStages LDS stages, each wave
+// fetching 1/8 of a tile; one s_barrier per tile publishes a landed tile and frees the
+// stage of the tile before last.  Between barriers the 8 waves run freely, so the two
+// waves of a SIMD fill each other's VALU and MFMA gaps.
+template <int D>
+__device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem& it, unsigned char* smem) {
+  constexpr int NSTEP = D / 16, NDB = D / 32;
+  constexpr int BLK_LDS = 16 * D * 2;     // bytes of one (block, head)
+  constexpr int KT_BYTES = 4 * BLK_LDS;   // K (or V) tile: 64 keys
+  constexpr int STAGE = 2 * KT_BYTES;
+  constexpr int kStages = 4, kAhead = kStages - 1;
+  constexpr int UPW = D / 64;             // 1-KiB units of K (and of V) each wave fetches per tile
+  constexpr int UPB = BLK_LDS / 1024;     // units per block
+  constexpr int NI = 2 * UPW;             // DMA instructions per wave per tile
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, half = lane >> 5, c32 = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const SeqInfo si = p.seqs[it.seq];
+  const int gi_n = it.n_heads;
+  const int rows_valid = it.n_tok * gi_n;
+  const int row_base = wave * 32;
+  const bool wave_has_rows = row_base < rows_valid;
+  const int kv_len = si.prefix_len + si.chunk_len;
+  const int pos0 = si.prefix_len + it.q_tok0;
+  const float c = p.scale_log2e;
+  const int wave_min_limit = pos0 + min(row_base, rows_valid - 1) / gi_n;
+  const int wave_max_limit = wave_has_rows ? pos0 + min(row_base + 31, rows_valid - 1) / gi_n : -1;
+
+  const int r = min(row_base + c32, rows_valid - 1);
+  const int t_row = r / gi_n, gi_row = r - t_row * gi_n;
+  const int limit = pos0 + t_row;
+  bf16x8 qreg[NSTEP];
+  {
+    const unsigned short* qp =
+        p.q + ((long long)(si.q_off + it.q_tok0 + t_row) * p.n_q_heads + it.head0 + gi_row) * D + 8 * half;
+#pragma unroll
+    for (int s = 0; s < NSTEP; ++s) {
+      u32x4 qv = *reinterpret_cast<const u32x4*>(qp + 16 * s);
+      asm volatile("" : "+v"(qv));  // wait for the load here, not inside the pipeline
+      qreg[s] = as_bf16x8(qv);
+    }
+  }
+  f32x16 o[NDB];
+  float m = kNeg, l = 0.f;
+#pragma unroll
+  for (int db = 0; db < NDB; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
+
+  const int* bt = p.block_tables + (long long)it.seq * p.max_blocks;
+  const long long head_stride = (long long)BLK_LDS;
+  const int n_sub = (it.kv_end - it.kv_begin + 31) >> 5;  // kv_begin = 0 for wide items
+  const int last_blk = si.n_blocks - 1;
+  const int pr = perm32(c32);
+
+  // ---- DMA of tile j: this wave moves UPW units of K and of V, all inside one block
+  const int blk_w = (wave * UPW) / UPB, part_w = (wave * UPW) % UPB;
+  lds_byte* const lds0 = (lds_byte*)smem;
+  int bt_reg = 0;  // lane i: physical block of this wave's share of tile (64*k + i)
+  auto issue_tile = [&](int j) {
+    if ((j & 63) == 0) {
+      bt_reg = bt[min(4 * (j + lane) + blk_w, last_blk)];
+      asm volatile("" : "+v"(bt_reg));
+    }
+    const long long b = __builtin_amdgcn_readlane(bt_reg, j & 63);
+    const long long goff = (b * p.n_kv_heads + it.kv_head) * head_stride + part_w * 1024 + lane * 16;
+    lds_byte* dst = lds0 + (j % kStages) * STAGE + blk_w * BLK_LDS + part_w * 1024;
+#pragma unroll
+    for (int x = 0; x < UPW; ++x) {
+      __builtin_amdgcn_global_load_lds(p.k_pool + goff + x * 1024, dst + x * 1024, 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(p.v_pool + goff + x * 1024, dst + KT_BYTES + x * 1024, 16, 0, 0);
+    }
+  };
+
+  // ---- LDS operand reads (byte addresses)
+  const unsigned lds_base = (unsigned)(unsigned long long)lds0;
+  const unsigned k_lane = lds_base + (pr >> 4) * BLK_LDS + (half * 16 + (pr & 15)) * 16;
+  const unsigned v_lane = lds_base + KT_BYTES + (half * D + pr) * 16;
+  u32x4 ka[NSTEP], va[NSTEP];
+  auto read_k = [&](int u) {
+    const unsigned a = k_lane + ((u >> 1) % kStages) * STAGE + (u & 1) * 2 * BLK_LDS;
+    lds_read128<0>(ka[0], a);
+    lds_read128<512>(ka[1], a);
+    lds_read128<1024>(ka[2], a);
+    lds_read128<1536>(ka[3], a);
+    if constexpr (NSTEP == 8) {
+      lds_read128<2048>(ka[4], a);
+      lds_read128<2560>(ka[5], a);
+      lds_read128<3072>(ka[6], a);
+      lds_read128<3584>(ka[7], a);
+    }
+  };
+  auto read_v = [&](int u) {
+    const unsigned a = v_lane + ((u >> 1) % kStages) * STAGE + (u & 1) * 2 * BLK_LDS;
+    if constexpr (NDB == 4) {
+      lds_read128<0>(va[0], a);
+      lds_read128<512>(va[1], a);
+      lds_read128<1024>(va[2], a);
+      lds_read128<1536>(va[3], a);
+      lds_read128<BLK_LDS>(va[4], a);
+      lds_read128<BLK_LDS + 512>(va[5], a);
+      lds_read128<BLK_LDS + 1024>(va[6], a);
+      lds_read128<BLK_LDS + 1536>(va[7], a);
+    } else {
+      lds_read128<0>(va[0], a);
+      lds_read128<512>(va[1], a);
+      lds_read128<BLK_LDS>(va[2], a);
+      lds_read128<BLK_LDS + 512>(va[3], a);
+    }
+  };
+  auto active = [&](int u) { return 32 * u <= wave_max_limit; };
+
+  u32x4 pp[2];
+  auto qk = [&](f32x16& s) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s[i] = 0.f;
+#pragma unroll
+    for (int st = 0; st < NSTEP; ++st)
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ka[st]), qreg[st], s, 0, 0, 0);
+  };
+
+  // ---- prologue: first tiles in flight, tile 0 landed everywhere, S(0), K(1) on its way
+#pragma unroll
+  for (int j = 0; j < kAhead; ++j) issue_tile(j);
+  wait_vmcnt<NI * (kAhead - 1)>();
+  __builtin_amdgcn_s_barrier();
+  f32x16 s_even, s_odd;  // S(u) of even / odd sub-tiles
+  read_k(0);
+  lds_wait(ka);
+  if (active(0)) qk(s_even);
+  if (n_sub > 1) read_k(1);
+
+  // one sub-tile: s_cur = S(u) is consumed, s_nxt receives S(u+1)
+  auto step = [&](int u, f32x16& s_cur, f32x16& s_nxt, bool opens_tile) {
+    const int sub_base = 32 * u;
+    const bool act = active(u);
+    lds_wait(ka);                                     // K(u+1) operands are in registers
+    if (u + 1 < n_sub && active(u + 1)) qk(s_nxt);    // S(u+1): MFMA work that overlaps the softmax below
+    read_v(u);
+    if (act) softmax_tile<NDB>(s_cur, sub_base + 31 > wave_min_limit, sub_base, half, limit, c, m, l, o, pp);
+    lds_wait(va);
+    if (u + 2 < n_sub) {
+      if (opens_tile) {
+        // K(u+2) opens tile u/2 + 1: this wave's share of it has landed (the tile after it
+        // may still be in flight); the barrier publishes it and tells that every wave is
+        // done reading tile u/2 - 1, whose stage the next fetch overwrites
+        wait_vmcnt<NI>();
+        __builtin_amdgcn_s_barrier();
+        issue_tile((u >> 1) + kAhead);
+      }
+      read_k(u + 2);
+    }
+    if (act) {
+      if (sub_base + 32 > kv_len) {  // slots past the sequence's length hold anything
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int db = 0; db < NDB; ++db)
+            va[t * NDB + db] = zero_tail(va[t * NDB + db], sub_base + 16 * t + 8 * half, kv_len);
+      }
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va[t * NDB + db]), as_bf16x8(pp[t]), o[db], 0, 0, 0);
+    }
+  };
+  for (int u = 0; u < n_sub; u += 2) {
+    step(u, s_even, s_odd, true);
+    if (u + 1 < n_sub) step(u + 1, s_odd, s_even, false);
+  }
+  wait_vmcnt<0>();  // fetches past the item's last tile are still landing in LDS
+  __builtin_amdgcn_s_barrier();
+
+  const float lt = pair_sum(l);
+  if (row_base + c32 < rows_valid) {
+    unsigned short* op = p.out + ((long long)(si.q_off + it.q_tok0 + t_row) * p.n_q_heads + it.head0 + gi_row) * D;
+    store_row_bf16<NDB>(op, o, 1.0f / lt, half);
+  }
+}
+
 // --------------------------------------------------------- narrow (decode-like) item
 template <int D, bool FP8>
 struct NarrowOps {
@@ -340,42 +560,21 @@ struct NarrowOps {
   typename RawChunk<FP8>::type v[2 * (D / 32)];
 };
 
-typedef __attribute__((address_space(3))) unsigned char lds_byte;
-
-// LDS reads of data that arrived by global_load_lds.  They are written as asm so that
-// the waits on those loads are the explicit s_waitcnt below and nothing coarser.
-#define CRONUS_LDS_READ128(dst, addr, OFF) \
-  asm volatile("ds_read_b128 %0, %1 offset:" #OFF : "=v"(dst) : "v"(addr) : "memory")
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-  static_assert(N == 0 || N == 4 || N == 8, "counts used by the narrow pipeline");
-  if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-  if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-}
-
-// Read the NOPS 1-KiB operand planes of this lane (plane n at addr + 1024 n) and wait
-// for them; the "+v" operands tie the wait to the registers the MFMAs consume.
+// Read the NOPS 1-KiB operand planes of this lane (plane n at addr + 1024 n) and wait.
 template <int NOPS>
 __device__ __forceinline__ void lds_read_planes(u32x4 (&x)[NOPS], unsigned addr) {
   static_assert(NOPS == 4 || NOPS == 8, "D = 64 or 128");
-  CRONUS_LDS_READ128(x[0], addr, 0);
-  CRONUS_LDS_READ128(x[1], addr, 1024);
-  CRONUS_LDS_READ128(x[2], addr, 2048);
-  CRONUS_LDS_READ128(x[3], addr, 3072);
+  lds_read128<0>(x[0], addr);
+  lds_read128<1024>(x[1], addr);
+  lds_read128<2048>(x[2], addr);
+  lds_read128<3072>(x[3], addr);
   if constexpr (NOPS == 8) {
-    CRONUS_LDS_READ128(x[4], addr, 4096);
-    CRONUS_LDS_READ128(x[5], addr, 5120);
-    CRONUS_LDS_READ128(x[6], addr, 6144);
-    CRONUS_LDS_READ128(x[7], addr, 7168);
-    asm volatile("s_waitcnt lgkmcnt(0)"
-                 : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7])
-                 :
-                 : "memory");
-  } else {
-    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]) : : "memory");
+    lds_read128<4096>(x[4], addr);
+    lds_read128<5120>(x[5], addr);
+    lds_read128<6144>(x[6], addr);
+    lds_read128<7168>(x[7], addr);
   }
+  lds_wait(x);
 }
 
 template <int D, bool FP8>
@@ -553,7 +752,7 @@ __device__ __forceinline__ void run_narrow(const AttnParams& p, const WorkItem& 
     }
   }
 
-  // combine the four waves (each covered different keys) in wave 0: every wave parks its
+  // combine the waves (each covered different keys) in wave 0: every wave parks its
   // accumulators in its own LDS planes (its reads of them are complete)
   float* xo = reinterpret_cast<float*>(smem + wave * WAVE_LDS) + lane;        // [NACC][64]
   float* xs = reinterpret_cast<float*>(smem + kWaves * WAVE_LDS) + lane;      // [kWaves][2][64]
@@ -609,12 +808,16 @@ __device__ __forceinline__ void run_narrow(const AttnParams& p, const WorkItem& 
   }
 }
 
-template <int D, bool FP8, int QT>
-__global__ __launch_bounds__(kThreads, 2) void attn_mixed_kernel(AttnParams p) {
+template <int D, bool FP8>
+__global__ __launch_bounds__(kThreads) void attn_mixed_kernel(AttnParams p) {
   extern __shared__ __align__(16) unsigned char smem[];
   const WorkItem it = p.items[blockIdx.x];
-  if (it.wide) run_wide<D, FP8, QT>(p, it, smem);
-  else run_narrow<D, FP8>(p, it, smem);
+  if (it.wide) {
+    if constexpr (FP8) run_wide_staged<D, FP8, 1>(p, it, smem);
+    else run_wide_dma<D>(p, it, smem);
+  } else {
+    run_narrow<D, FP8>(p, it, smem);
+  }
 }
 
 // Combine the partial results of a row group that was split over key spans:
@@ -647,15 +850,14 @@ __global__ __launch_bounds__(D) void attn_merge_kernel(AttnParams p) {
 
 template <int D, bool FP8>
 int launch_typed(const AttnLaunch& a, const AttnParams& p) {
-  constexpr int QT = CRONUS_WIDE_QT;
-  constexpr int wide_lds = 2 * 2 * 4 * 16 * D * 2;
+  constexpr int wide_lds = (FP8 ? 2 : 4) * 2 * 4 * 16 * D * 2;  // stages x (K + V tile of 64 keys)
   constexpr int narrow_lds = kWaves * (2 * (D / 16) * 1024) + kWaves * 2 * 64 * 4;
   constexpr int lds = wide_lds > narrow_lds ? wide_lds : narrow_lds;
   static_assert(lds <= 160 * 1024, "LDS budget");
   hipStream_t s = static_cast<hipStream_t>(a.stream);
   const Plan& pl = *a.plan;
   if (pl.n_items > 0) {
-    auto kern = attn_mixed_kernel<D, FP8, QT>;
+    auto kern = attn_mixed_kernel<D, FP8>;
     static bool attr_set = false;
     if (!attr_set) {
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
@@ -678,7 +880,7 @@ int launch_typed(const AttnLaunch& a, const AttnParams& p) {
 
 }  // namespace
 
-int wide_rows_for(int /*head_dim*/, int /*kv_dtype*/) { return kWaves * 32 * CRONUS_WIDE_QT; }
+int wide_rows_for(int /*head_dim*/, int /*kv_dtype*/) { return kWaves * 32; }
 
 int launch_attn(const AttnLaunch& a) {
   const cronus_kv_cache& c = *a.cache;

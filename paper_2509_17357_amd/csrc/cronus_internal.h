@@ -10,11 +10,11 @@
 namespace cronus {
 
 constexpr int kBlock = 16;          // tokens per KV block (N_size of Algorithm 1)
-constexpr int kThreads = 256;       // 4 wavefronts of 64 lanes per work-group
-constexpr int kWaves = 4;
+constexpr int kThreads = 512;       // 8 wavefronts of 64 lanes per work-group: two per SIMD
+constexpr int kWaves = 8;
 constexpr int kNarrowRows = 32;     // one MFMA column tile: a decode's (token, head) rows
 constexpr int kWideKvTile = 64;     // keys staged in LDS per step of a wide (chunk) tile
-constexpr int kNarrowKvStep = 32 * kWaves;  // keys covered by the 4 waves of a narrow item per step
+constexpr int kNarrowKvStep = 32 * kWaves;  // keys covered by the waves of a narrow item per step
 
 // Per-sequence record of the batch (section 4.4: one iteration = chunks + decodes).
 struct SeqInfo {
