@@ -35,7 +35,7 @@ struct WorkItem {
   int32_t kv_begin;  // keys [kv_begin, kv_end) are processed by this item
   int32_t kv_end;
   int32_t partial;   // < 0: writes final output; else index of its partial-result slot
-  int32_t wide;      // 1: chunk tile staged through LDS; 0: narrow (<= 32 rows), waves split keys
+  int32_t wide;      // 1: chunk tile staged through LDS; 0: narrow (<= 32 rows), waves split keys; -1: idle slot
   int32_t pad0, pad1;
 };
 

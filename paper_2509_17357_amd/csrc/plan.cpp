@@ -106,8 +106,55 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
       }
     }
   }
-  // longest first: the hardware hands out work-groups in index order
-  std::stable_sort(items.begin(), items.end(), [](const Costed& a, const Costed& b) { return a.cost > b.cost; });
+  // Order for the grid.  Work-group i runs on XCD i % 8 (each XCD has its own L2) and an
+  // XCD takes its work-groups in index order.  All wide tiles of one (sequence, KV head)
+  // read the same K/V blocks, so they are queued on one XCD, back to back, where the
+  // 32 CUs of that XCD run them side by side and share the blocks through its L2.
+  // Groups go to the least loaded XCD, longest first; narrow items (no reuse) even out
+  // the queues.  Queues are padded to one length with idle items (wide = -1).
+  constexpr int kXcds = 8;
+  std::vector<std::vector<Costed>> queue(kXcds);
+  double load[kXcds] = {0};
+  {
+    struct Group { double cost = 0; std::vector<Costed> items; };
+    std::vector<Group> groups;
+    std::vector<Costed> narrow;
+    long long last_key = -1;
+    for (const Costed& c : items) {  // wide tiles of a group were generated consecutively
+      if (!c.item.wide) { narrow.push_back(c); continue; }
+      const long long key = ((long long)c.item.seq * Hkv + c.item.kv_head) * 64 + (c.item.head0 % G) / group;
+      if (key != last_key) { groups.emplace_back(); last_key = key; }
+      groups.back().items.push_back(c);
+      groups.back().cost += c.cost;
+    }
+    std::stable_sort(groups.begin(), groups.end(), [](const Group& a, const Group& b) { return a.cost > b.cost; });
+    for (Group& g : groups) {
+      int x = 0;
+      for (int i = 1; i < kXcds; ++i) if (load[i] < load[x]) x = i;
+      std::stable_sort(g.items.begin(), g.items.end(), [](const Costed& a, const Costed& b) { return a.cost > b.cost; });
+      queue[x].insert(queue[x].end(), g.items.begin(), g.items.end());
+      load[x] += g.cost;
+    }
+    std::stable_sort(narrow.begin(), narrow.end(), [](const Costed& a, const Costed& b) { return a.cost > b.cost; });
+    for (const Costed& c : narrow) {
+      int x = 0;
+      for (int i = 1; i < kXcds; ++i) if (load[i] < load[x]) x = i;
+      queue[x].push_back(c);
+      load[x] += c.cost;
+    }
+  }
+  size_t qlen = 0;
+  for (const auto& q : queue) qlen = std::max(qlen, q.size());
+  const size_t n_real_items = items.size();
+  items.clear();
+  if (n_real_items) {
+    WorkItem idle{};
+    idle.wide = -1;
+    idle.partial = -1;
+    for (size_t k = 0; k < qlen; ++k)
+      for (int x = 0; x < kXcds; ++x) items.push_back(k < queue[x].size() ? queue[x][k] : Costed{idle, 0.0});
+    while (!items.empty() && items.back().item.wide < 0) items.pop_back();  // trailing idle slots
+  }
 
   plan->n_seqs = n_seqs;
   plan->wide_rows = wide_rows;
