@@ -346,24 +346,30 @@ __device__ __forceinline__ void wait_vmcnt() {
   if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
 }
 
-// LDS reads of data that arrived by global_load_lds are written as asm: the waits on
-// those loads are then the explicit s_waitcnt of the pipeline and nothing coarser.
-template <int OFF>
-__device__ __forceinline__ void lds_read128(u32x4& dst, unsigned addr) {
-  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "i"(OFF) : "memory");
+// LDS reads of data that arrived by global_load_lds are written as asm, so that the
+// waits on those loads are the explicit vmcnt waits of the pipelines and nothing coarser
+// (the compiler would wait for every DMA in flight before any LDS read).  The reads and
+// the wait for them form ONE asm statement: its outputs are valid when it ends, so no
+// register copy the compiler may insert afterwards can see a value that has not arrived.
+template <int O0, int O1, int O2, int O3>
+__device__ __forceinline__ void lds_read4(u32x4& x0, u32x4& x1, u32x4& x2, u32x4& x3, unsigned addr) {
+  asm volatile(
+      "ds_read_b128 %0, %4 offset:%5\n\tds_read_b128 %1, %4 offset:%6\n\t"
+      "ds_read_b128 %2, %4 offset:%7\n\tds_read_b128 %3, %4 offset:%8\n\ts_waitcnt lgkmcnt(0)"
+      : "=&v"(x0), "=&v"(x1), "=&v"(x2), "=&v"(x3)
+      : "v"(addr), "i"(O0), "i"(O1), "i"(O2), "i"(O3)
+      : "memory");
 }
-// Wait for every LDS read issued so far; the "+v" operands tie the wait to the
-// registers that the following MFMAs consume.
-template <int N>
-__device__ __forceinline__ void lds_wait(u32x4 (&x)[N]) {
-  static_assert(N == 4 || N == 8, "D = 64 or 128");
-  if constexpr (N == 8)
-    asm volatile("s_waitcnt lgkmcnt(0)"
-                 : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7])
-                 :
-                 : "memory");
-  else
-    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]) : : "memory");
+template <int O0, int O1, int O2, int O3, int O4, int O5, int O6, int O7>
+__device__ __forceinline__ void lds_read8(u32x4 (&x)[8], unsigned addr) {
+  asm volatile(
+      "ds_read_b128 %0, %8 offset:%9\n\tds_read_b128 %1, %8 offset:%10\n\t"
+      "ds_read_b128 %2, %8 offset:%11\n\tds_read_b128 %3, %8 offset:%12\n\t"
+      "ds_read_b128 %4, %8 offset:%13\n\tds_read_b128 %5, %8 offset:%14\n\t"
+      "ds_read_b128 %6, %8 offset:%15\n\tds_read_b128 %7, %8 offset:%16\n\ts_waitcnt lgkmcnt(0)"
+      : "=&v"(x[0]), "=&v"(x[1]), "=&v"(x[2]), "=&v"(x[3]), "=&v"(x[4]), "=&v"(x[5]), "=&v"(x[6]), "=&v"(x[7])
+      : "v"(addr), "i"(O0), "i"(O1), "i"(O2), "i"(O3), "i"(O4), "i"(O5), "i"(O6), "i"(O7)
+      : "memory");
 }
 
 // Schedule per wave (n = number of 32-key sub-tiles, S(u) = K(u) Q^T, P(u) = softmax
@@ -453,34 +459,14 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
   u32x4 ka[NSTEP], va[NSTEP];
   auto read_k = [&](int u) {
     const unsigned a = k_lane + ((u >> 1) % kStages) * STAGE + (u & 1) * 2 * BLK_LDS;
-    lds_read128<0>(ka[0], a);
-    lds_read128<512>(ka[1], a);
-    lds_read128<1024>(ka[2], a);
-    lds_read128<1536>(ka[3], a);
-    if constexpr (NSTEP == 8) {
-      lds_read128<2048>(ka[4], a);
-      lds_read128<2560>(ka[5], a);
-      lds_read128<3072>(ka[6], a);
-      lds_read128<3584>(ka[7], a);
-    }
+    if constexpr (NSTEP == 8) lds_read8<0, 512, 1024, 1536, 2048, 2560, 3072, 3584>(ka, a);
+    else lds_read4<0, 512, 1024, 1536>(ka[0], ka[1], ka[2], ka[3], a);
   };
   auto read_v = [&](int u) {
     const unsigned a = v_lane + ((u >> 1) % kStages) * STAGE + (u & 1) * 2 * BLK_LDS;
-    if constexpr (NDB == 4) {
-      lds_read128<0>(va[0], a);
-      lds_read128<512>(va[1], a);
-      lds_read128<1024>(va[2], a);
-      lds_read128<1536>(va[3], a);
-      lds_read128<BLK_LDS>(va[4], a);
-      lds_read128<BLK_LDS + 512>(va[5], a);
-      lds_read128<BLK_LDS + 1024>(va[6], a);
-      lds_read128<BLK_LDS + 1536>(va[7], a);
-    } else {
-      lds_read128<0>(va[0], a);
-      lds_read128<512>(va[1], a);
-      lds_read128<BLK_LDS>(va[2], a);
-      lds_read128<BLK_LDS + 512>(va[3], a);
-    }
+    if constexpr (NSTEP == 8)
+      lds_read8<0, 512, 1024, 1536, BLK_LDS, BLK_LDS + 512, BLK_LDS + 1024, BLK_LDS + 1536>(va, a);
+    else lds_read4<0, 512, BLK_LDS, BLK_LDS + 512>(va[0], va[1], va[2], va[3], a);
   };
   auto active = [&](int u) { return 32 * u <= wave_max_limit; };
 
@@ -500,7 +486,6 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
   __builtin_amdgcn_s_barrier();
   f32x16 s_even, s_odd;  // S(u) of even / odd sub-tiles
   read_k(0);
-  lds_wait(ka);
   if (active(0)) qk(s_even);
   if (n_sub > 1) read_k(1);
 
@@ -508,11 +493,9 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
   auto step = [&](int u, f32x16& s_cur, f32x16& s_nxt, bool opens_tile) {
     const int sub_base = 32 * u;
     const bool act = active(u);
-    lds_wait(ka);                                     // K(u+1) operands are in registers
     if (u + 1 < n_sub && active(u + 1)) qk(s_nxt);    // S(u+1): MFMA work that overlaps the softmax below
-    read_v(u);
     if (act) softmax_tile<NDB>(s_cur, sub_base + 31 > wave_min_limit, sub_base, half, limit, c, m, l, o, pp);
-    lds_wait(va);
+    read_v(u);
     if (u + 2 < n_sub) {
       if (opens_tile) {
         // K(u+2) opens tile u/2 + 1: this wave's share of it has landed (the tile after it
@@ -560,21 +543,12 @@ struct NarrowOps {
   typename RawChunk<FP8>::type v[2 * (D / 32)];
 };
 
-// Read the NOPS 1-KiB operand planes of this lane (plane n at addr + 1024 n) and wait.
+// Read the NOPS 1-KiB operand planes of this lane (plane n at addr + 1024 n).
 template <int NOPS>
 __device__ __forceinline__ void lds_read_planes(u32x4 (&x)[NOPS], unsigned addr) {
   static_assert(NOPS == 4 || NOPS == 8, "D = 64 or 128");
-  lds_read128<0>(x[0], addr);
-  lds_read128<1024>(x[1], addr);
-  lds_read128<2048>(x[2], addr);
-  lds_read128<3072>(x[3], addr);
-  if constexpr (NOPS == 8) {
-    lds_read128<4096>(x[4], addr);
-    lds_read128<5120>(x[5], addr);
-    lds_read128<6144>(x[6], addr);
-    lds_read128<7168>(x[7], addr);
-  }
-  lds_wait(x);
+  if constexpr (NOPS == 8) lds_read8<0, 1024, 2048, 3072, 4096, 5120, 6144, 7168>(x, addr);
+  else lds_read4<0, 1024, 2048, 3072>(x[0], x[1], x[2], x[3], addr);
 }
 
 template <int D, bool FP8>
@@ -812,6 +786,7 @@ template <int D, bool FP8>
 __global__ __launch_bounds__(kThreads) void attn_mixed_kernel(AttnParams p) {
   extern __shared__ __align__(16) unsigned char smem[];
   const WorkItem it = p.items[blockIdx.x];
+  if (it.wide < 0 || it.n_tok <= 0 || it.n_heads <= 0) return;  // idle slot that keeps the XCD queues aligned
   if (it.wide) {
     if constexpr (FP8) run_wide_staged<D, FP8, 1>(p, it, smem);
     else run_wide_dma<D>(p, it, smem);
