@@ -22,6 +22,10 @@
 
 #include "cronus_internal.h"
 
+#ifndef CRONUS_HINT
+#define CRONUS_HINT 7  // VALU instructions issued per MFMA in the interleaved block
+#endif
+
 namespace cronus {
 namespace {
 
@@ -113,9 +117,11 @@ __device__ __forceinline__ u32x4 to_bf16_chunk(typename RawChunk<FP8>::type c) {
 // Online softmax update of one 32(q) x 32(key) S^T tile held as 16 accumulators per
 // lane.  key of accumulator i = sub_base + 16*(i/8) + 8*half + i%8.
 // Returns the two P^T operands (keys 0-15 and 16-31 of the sub-tile).
+// First part: causal mask, running maximum (rescales O and l when some row's maximum
+// grew).  Second part: numerators, their row sum, and the bf16 P^T operands.
 template <int NDB>
-__device__ __forceinline__ void softmax_tile(f32x16& s, bool need_mask, int sub_base, int half, int limit,
-                                             float c, float& m, float& l, f32x16 (&o)[NDB], u32x4 (&p)[2]) {
+__device__ __forceinline__ void softmax_max_part(f32x16& s, bool need_mask, int sub_base, int half, int limit,
+                                                 float c, float& m, float& l, f32x16 (&o)[NDB]) {
   if (need_mask) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -137,19 +143,26 @@ __device__ __forceinline__ void softmax_tile(f32x16& s, bool need_mask, int sub_
       for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
     m = m_new;
   }
+}
+__device__ __forceinline__ void softmax_exp_part(const f32x16& s, float c, float m, float& l, u32x4 (&p)[2]) {
   const float mc = m * c;
   float sum = 0.f;
-  float e[16];
-#pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    e[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c, -mc));
-    sum += e[i];
-  }
-  l += sum;
 #pragma unroll
   for (int t = 0; t < 2; ++t)
 #pragma unroll
-    for (int w = 0; w < 4; ++w) p[t][w] = pack_bf16(e[8 * t + 2 * w], e[8 * t + 2 * w + 1]);
+    for (int w = 0; w < 4; ++w) {
+      const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * t + 2 * w], c, -mc));
+      const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * t + 2 * w + 1], c, -mc));
+      sum += e0 + e1;
+      p[t][w] = pack_bf16(e0, e1);
+    }
+  l += sum;
+}
+template <int NDB>
+__device__ __forceinline__ void softmax_tile(f32x16& s, bool need_mask, int sub_base, int half, int limit,
+                                             float c, float& m, float& l, f32x16 (&o)[NDB], u32x4 (&p)[2]) {
+  softmax_max_part<NDB>(s, need_mask, sub_base, half, limit, c, m, l, o);
+  softmax_exp_part(s, c, m, l, p);
 }
 
 // Store one lane's share of a finished row: dims 32*db + 16*j + 8*half + 0..7.
@@ -522,7 +535,44 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
           o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va[t * NDB + db]), as_bf16x8(pp[t]), o[db], 0, 0, 0);
     }
   };
-  for (int u = 0; u < n_sub; u += 2) {
+  // Steady state: sub-tiles that this wave sees whole (no causal mask, no tail) and that
+  // are followed by two more.  No conditionals besides the once-per-tile hand-over, so
+  // the S(u+1) products and the exponentials of S(u), which are independent, sit in one
+  // block and are interleaved: the wave keeps issuing VALU work while each MFMA of the
+  // dependent chain is in the pipe.
+  auto fast_step = [&](int u, f32x16& s_cur, f32x16& s_nxt, bool opens_tile) {
+    softmax_max_part<NDB>(s_cur, false, 32 * u, half, limit, c, m, l, o);
+    qk(s_nxt);
+    softmax_exp_part(s_cur, c, m, l, pp);
+#if CRONUS_HINT
+#pragma unroll
+    for (int i = 0; i < NSTEP; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x402, CRONUS_HINT, 0);
+    }
+#endif
+    read_v(u);
+    if (opens_tile) {
+      wait_vmcnt<NI>();
+      __builtin_amdgcn_s_barrier();
+      issue_tile((u >> 1) + kAhead);
+    }
+    read_k(u + 2);
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va[t * NDB + db]), as_bf16x8(pp[t]), o[db], 0, 0, 0);
+  };
+  // sub-tile u is "whole" for this wave when u + 1 is too: 32 (u + 1) + 31 <= wave_min_limit
+  int n_fast = wave_has_rows ? min(n_sub - 2, (wave_min_limit + 1) / 32 - 1) : 0;
+  n_fast = max(n_fast, 0) & ~1;
+  int u = 0;
+  for (; u < n_fast; u += 2) {
+    fast_step(u, s_even, s_odd, true);
+    fast_step(u + 1, s_odd, s_even, false);
+  }
+  for (; u < n_sub; u += 2) {
     step(u, s_even, s_odd, true);
     if (u + 1 < n_sub) step(u + 1, s_odd, s_even, false);
   }
