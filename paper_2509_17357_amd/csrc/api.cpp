@@ -107,7 +107,7 @@ size_t cronus_attn_mixed_workspace_bytes(const cronus_kv_cache* cache, const int
                                          const int32_t* chunk_lens, int32_t n_seqs) {
   if (check_shape(cache) || n_seqs < 0 || (n_seqs > 0 && (!prefix_lens || !chunk_lens))) return 0;
   Plan plan;
-  if (build_plan(cache, prefix_lens, chunk_lens, n_seqs, 0x7fffffff / kBlock, device_cus(), &plan, nullptr)) return 0;
+  if (build_plan(cache, prefix_lens, chunk_lens, n_seqs, 0x7fffffff / kBlock, device_cus(), &plan)) return 0;
   return plan.total_bytes;
 }
 
@@ -116,7 +116,7 @@ int cronus_attn_mixed_plan_stats(const cronus_kv_cache* cache, const int32_t* pr
   if (int rc = check_shape(cache)) return rc;
   if (!stats || n_seqs < 0 || (n_seqs > 0 && (!prefix_lens || !chunk_lens))) return CRONUS_ERR_INVALID_ARG;
   Plan plan;
-  if (int rc = build_plan(cache, prefix_lens, chunk_lens, n_seqs, 0x7fffffff / kBlock, device_cus(), &plan, nullptr))
+  if (int rc = build_plan(cache, prefix_lens, chunk_lens, n_seqs, 0x7fffffff / kBlock, device_cus(), &plan))
     return rc;
   stats[0] = plan.n_items;
   stats[1] = plan.n_wide;
@@ -143,7 +143,7 @@ int cronus_attn_mixed(const cronus_kv_cache* cache, const void* q, void* out, co
 
   Plan plan;
   const int n_cus = device_cus();
-  if (int rc = build_plan(cache, prefix_lens, chunk_lens, n_seqs, max_blocks_per_seq, n_cus, &plan, nullptr)) return rc;
+  if (int rc = build_plan(cache, prefix_lens, chunk_lens, n_seqs, max_blocks_per_seq, n_cus, &plan)) return rc;
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return CRONUS_ERR_WORKSPACE;
   if (workspace_bytes < plan.total_bytes) return CRONUS_ERR_WORKSPACE;
   if (plan.n_items > 0x7fffffffLL) return CRONUS_ERR_INVALID_ARG;
@@ -153,8 +153,7 @@ int cronus_attn_mixed(const cronus_kv_cache* cache, const void* q, void* out, co
     std::lock_guard<std::mutex> lock(g_mu);
     Slot* slot = acquire_slot(plan.upload_bytes);
     if (!slot) return CRONUS_ERR_HIP;
-    if (int rc = build_plan(cache, prefix_lens, chunk_lens, n_seqs, max_blocks_per_seq, n_cus, &plan, slot->host))
-      return rc;
+    write_plan(&plan, slot->host);
     if (hipMemcpyAsync(workspace, slot->host, plan.upload_bytes, hipMemcpyHostToDevice, stream) != hipSuccess)
       return CRONUS_ERR_HIP;
     if (hipEventRecord(slot->done, stream) != hipSuccess) return CRONUS_ERR_HIP;

@@ -67,10 +67,12 @@ inline size_t partial_floats(int head_dim) { return (size_t)kNarrowRows * (head_
 // Rows per wide tile for a head shape (must match the kernel instance that is launched).
 int wide_rows_for(int head_dim, int kv_dtype);
 
-// Builds the work decomposition.  If `host_buf` is null only sizes are computed.
-// `host_buf` must hold plan->upload_bytes bytes (call once with null to learn it).
+// Builds the work decomposition (sizes and offsets into *plan; the work list itself stays
+// in a per-thread scratch).  write_plan() then copies that list into host_buf, which must
+// hold plan->upload_bytes bytes; it must follow build_plan() on the same thread.
 int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const int32_t* chunk_lens,
-               int32_t n_seqs, int32_t max_blocks_per_seq, int n_cus, Plan* plan, void* host_buf);
+               int32_t n_seqs, int32_t max_blocks_per_seq, int n_cus, Plan* plan);
+void write_plan(const Plan* plan, void* host_buf);
 
 struct AttnLaunch {
   const cronus_kv_cache* cache;

@@ -3,6 +3,11 @@
 // context, decode cost with the summed decode contexts).  Chunks become wide tiles of
 // `wide_rows` (token, head) rows; decodes and short chunks become narrow items whose
 // key range is cut into spans so that long contexts spread over the chip.
+//
+// This runs on the host inside every cronus_attn_mixed call, so it is written to be a
+// few tens of microseconds for thousands of items: flat arrays kept per thread, no
+// comparison sorts over items (narrow items are bucketed by length, the wide tiles of a
+// group are generated in cost order).
 #include <algorithm>
 #include <cstring>
 #include <vector>
@@ -14,15 +19,32 @@ namespace {
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-struct Costed {
-  WorkItem item;
-  double cost;
+constexpr int kXcds = 8;
+
+struct Group {      // the wide tiles of one (sequence, KV head, head group): items [begin, end)
+  int32_t begin, end;
+  float cost;
 };
+
+struct Scratch {
+  std::vector<SeqInfo> seqs;
+  std::vector<WorkItem> wide, narrow;
+  std::vector<float> wide_cost;
+  std::vector<Group> groups;
+  std::vector<MergeItem> merges;
+  std::vector<int32_t> queue[kXcds];  // item references: >= 0 wide index, < 0 ~narrow index
+  std::vector<int32_t> order, bucket_start;
+};
+
+Scratch& scratch() {
+  static thread_local Scratch s;
+  return s;
+}
 
 }  // namespace
 
 int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const int32_t* chunk_lens,
-               int32_t n_seqs, int32_t max_blocks_per_seq, int n_cus, Plan* plan, void* host_buf) {
+               int32_t n_seqs, int32_t max_blocks_per_seq, int n_cus, Plan* plan) {
   const int D = cache->head_dim, Hq = cache->num_q_heads, Hkv = cache->num_kv_heads;
   const int G = Hq / Hkv;
   const int group = std::min(G, kNarrowRows);          // q heads handled together by one item
@@ -46,12 +68,17 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
   const long long target_items = (long long)std::max(n_cus, 1) * 8;
   long long span = (narrow_keys + target_items - 1) / target_items;
   span = (span + kNarrowKvStep - 1) / kNarrowKvStep * kNarrowKvStep;
-  span = std::min<long long>(std::max<long long>(span, 2 * kNarrowKvStep), 32 * kNarrowKvStep);
+  constexpr int kMaxSpanSteps = 16;  // spans are 2 .. 16 steps of kNarrowKvStep keys
+  span = std::min<long long>(std::max<long long>(span, 2 * kNarrowKvStep), kMaxSpanSteps * kNarrowKvStep);
 
-  std::vector<SeqInfo> seqs((size_t)n_seqs);
-  std::vector<Costed> items;
-  std::vector<MergeItem> merges;
-  int64_t n_partials = 0, n_wide = 0, n_merge_rows = 0;
+  Scratch& sc = scratch();
+  sc.seqs.resize((size_t)n_seqs);
+  sc.wide.clear();
+  sc.narrow.clear();
+  sc.wide_cost.clear();
+  sc.groups.clear();
+  sc.merges.clear();
+  int64_t n_partials = 0, n_merge_rows = 0;
   int32_t q_off = 0;
 
   auto add_narrow = [&](int s, int kvh, int head0, int nh, int q_tok0, int n_tok, int kv_total) {
@@ -60,7 +87,7 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
     const int per = (int)(((kv_total + n_split - 1) / n_split + kNarrowKvStep - 1) / kNarrowKvStep * kNarrowKvStep);
     n_split = (kv_total + per - 1) / per;
     if (n_split > 1) {
-      merges.push_back(MergeItem{(int32_t)n_partials, n_split, s, kvh, head0, nh, q_tok0, n_tok});
+      sc.merges.push_back(MergeItem{(int32_t)n_partials, n_split, s, kvh, head0, nh, q_tok0, n_tok});
       n_merge_rows += (int64_t)n_tok * nh;
     }
     for (int i = 0; i < n_split; ++i) {
@@ -70,13 +97,13 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
       w.kv_end = std::min(kv_total, (i + 1) * per);
       w.partial = n_split > 1 ? (int32_t)(n_partials++) : -1;
       w.wide = 0;
-      items.push_back({w, 0.5 * (w.kv_end - w.kv_begin)});
+      sc.narrow.push_back(w);
     }
   };
 
   for (int s = 0; s < n_seqs; ++s) {
     const int P = prefix_lens[s], C = chunk_lens[s];
-    seqs[(size_t)s] = SeqInfo{P, C, q_off, (P + C + kBlock - 1) / kBlock};
+    sc.seqs[(size_t)s] = SeqInfo{P, C, q_off, (P + C + kBlock - 1) / kBlock};
     q_off += C;
     if (C == 0) continue;
     for (int kvh = 0; kvh < Hkv; ++kvh) {
@@ -87,6 +114,7 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
           add_narrow(s, kvh, head0, nh, 0, C, P + C);
           continue;
         }
+        Group g{(int32_t)sc.wide.size(), 0, 0.f};
         for (int t0 = 0; t0 < C; t0 += wide_tok) {
           const int nt = std::min(wide_tok, C - t0);
           if (nt * group <= kNarrowRows) {
@@ -99,87 +127,121 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
           w.kv_end = P + t0 + nt;
           w.partial = -1;
           w.wide = 1;
-          const double rows_frac = std::max(0.25, (double)(nt * nh) / wide_rows);
-          items.push_back({w, (double)w.kv_end * (wide_rows / 128.0) * rows_frac});
-          ++n_wide;
+          const float rows_frac = std::max(0.25f, (float)(nt * nh) / wide_rows);
+          const float cost = (float)w.kv_end * (wide_rows / 128.0f) * rows_frac;
+          sc.wide.push_back(w);
+          sc.wide_cost.push_back(cost);
+          g.cost += cost;
         }
+        g.end = (int32_t)sc.wide.size();
+        if (g.end > g.begin) sc.groups.push_back(g);
       }
     }
   }
+
   // Order for the grid.  Work-group i runs on XCD i % 8 (each XCD has its own L2) and an
   // XCD takes its work-groups in index order.  All wide tiles of one (sequence, KV head)
-  // read the same K/V blocks, so they are queued on one XCD, back to back, where the
-  // 32 CUs of that XCD run them side by side and share the blocks through its L2.
-  // Groups go to the least loaded XCD, longest first; narrow items (no reuse) even out
-  // the queues.  Queues are padded to one length with idle items (wide = -1).
-  constexpr int kXcds = 8;
-  std::vector<std::vector<Costed>> queue(kXcds);
+  // read the same K/V blocks, so they are queued on one XCD, back to back, longest first
+  // (they were generated shortest first), where the 32 CUs of that XCD run them side by
+  // side and share the blocks through its L2.  Groups go to the least loaded XCD, longest
+  // group first; narrow items (no reuse), longest first, even out the queues.  Queues are
+  // padded to one length with idle items (wide = -1).
   double load[kXcds] = {0};
-  {
-    struct Group { double cost = 0; std::vector<Costed> items; };
-    std::vector<Group> groups;
-    std::vector<Costed> narrow;
-    long long last_key = -1;
-    for (const Costed& c : items) {  // wide tiles of a group were generated consecutively
-      if (!c.item.wide) { narrow.push_back(c); continue; }
-      const long long key = ((long long)c.item.seq * Hkv + c.item.kv_head) * 64 + (c.item.head0 % G) / group;
-      if (key != last_key) { groups.emplace_back(); last_key = key; }
-      groups.back().items.push_back(c);
-      groups.back().cost += c.cost;
+  for (auto& q : sc.queue) q.clear();
+  auto least_loaded = [&]() {
+    int x = 0;
+    for (int i = 1; i < kXcds; ++i) if (load[i] < load[x]) x = i;
+    return x;
+  };
+  std::sort(sc.groups.begin(), sc.groups.end(), [](const Group& a, const Group& b) { return a.cost > b.cost; });
+  double wide_total = 0;
+  for (const Group& g : sc.groups) wide_total += g.cost;
+  const double piece_max = wide_total / (2 * kXcds);  // balance before locality: no piece above half a fair share
+  for (const Group& g : sc.groups) {
+    const int n_tiles = g.end - g.begin;
+    int pieces = piece_max > 0 ? (int)(g.cost / piece_max) + 1 : 1;
+    pieces = std::max(1, std::min(pieces, n_tiles));
+    for (int pc = 0; pc < pieces; ++pc) {  // contiguous runs of tiles, longest keys first
+      const int hi = g.end - (int)((long long)n_tiles * pc / pieces);
+      const int lo = g.end - (int)((long long)n_tiles * (pc + 1) / pieces);
+      const int x = least_loaded();
+      for (int i = hi - 1; i >= lo; --i) {
+        sc.queue[x].push_back(i);
+        load[x] += sc.wide_cost[(size_t)i];
+      }
     }
-    std::stable_sort(groups.begin(), groups.end(), [](const Group& a, const Group& b) { return a.cost > b.cost; });
-    for (Group& g : groups) {
-      int x = 0;
-      for (int i = 1; i < kXcds; ++i) if (load[i] < load[x]) x = i;
-      std::stable_sort(g.items.begin(), g.items.end(), [](const Costed& a, const Costed& b) { return a.cost > b.cost; });
-      queue[x].insert(queue[x].end(), g.items.begin(), g.items.end());
-      load[x] += g.cost;
-    }
-    std::stable_sort(narrow.begin(), narrow.end(), [](const Costed& a, const Costed& b) { return a.cost > b.cost; });
-    for (const Costed& c : narrow) {
-      int x = 0;
-      for (int i = 1; i < kXcds; ++i) if (load[i] < load[x]) x = i;
-      queue[x].push_back(c);
-      load[x] += c.cost;
+  }
+  {  // narrow items by length, longest first: bucket sort on the number of kNarrowKvStep steps
+    const size_t n = sc.narrow.size();
+    sc.bucket_start.assign(kMaxSpanSteps + 2, 0);
+    auto steps_of = [&](const WorkItem& w) {
+      return std::min(kMaxSpanSteps, (w.kv_end - w.kv_begin + kNarrowKvStep - 1) / kNarrowKvStep);
+    };
+    for (const WorkItem& w : sc.narrow) ++sc.bucket_start[(size_t)(kMaxSpanSteps - steps_of(w)) + 1];
+    for (int b = 0; b <= kMaxSpanSteps; ++b) sc.bucket_start[(size_t)b + 1] += sc.bucket_start[(size_t)b];
+    sc.order.resize(n);
+    for (size_t i = 0; i < n; ++i) sc.order[(size_t)sc.bucket_start[(size_t)(kMaxSpanSteps - steps_of(sc.narrow[i]))]++] = (int32_t)i;
+    for (size_t k = 0; k < n; ++k) {
+      const int32_t i = sc.order[k];
+      const WorkItem& w = sc.narrow[(size_t)i];
+      const int x = least_loaded();
+      sc.queue[x].push_back(~i);
+      load[x] += 0.5 * (w.kv_end - w.kv_begin);
     }
   }
   size_t qlen = 0;
-  for (const auto& q : queue) qlen = std::max(qlen, q.size());
-  const size_t n_real_items = items.size();
-  items.clear();
-  if (n_real_items) {
-    WorkItem idle{};
-    idle.wide = -1;
-    idle.partial = -1;
-    for (size_t k = 0; k < qlen; ++k)
-      for (int x = 0; x < kXcds; ++x) items.push_back(k < queue[x].size() ? queue[x][k] : Costed{idle, 0.0});
-    while (!items.empty() && items.back().item.wide < 0) items.pop_back();  // trailing idle slots
+  for (const auto& q : sc.queue) qlen = std::max(qlen, q.size());
+  const size_t n_real = sc.wide.size() + sc.narrow.size();
+  size_t n_slots = 0;
+  if (n_real) {
+    n_slots = qlen * kXcds;
+    // trailing idle slots are dropped
+    while (n_slots > 0) {
+      const size_t k = (n_slots - 1) / kXcds, x = (n_slots - 1) % kXcds;
+      if (k < sc.queue[x].size()) break;
+      --n_slots;
+    }
   }
 
   plan->n_seqs = n_seqs;
   plan->wide_rows = wide_rows;
-  plan->n_items = (int64_t)items.size();
-  plan->n_wide = n_wide;
+  plan->n_items = (int64_t)n_slots;
+  plan->n_wide = (int64_t)sc.wide.size();
   plan->n_partials = n_partials;
-  plan->n_merge = (int64_t)merges.size();
+  plan->n_merge = (int64_t)sc.merges.size();
   plan->n_merge_rows = n_merge_rows;
   plan->off_seqs = 0;
   plan->off_items = align_up(plan->off_seqs + sizeof(SeqInfo) * (size_t)n_seqs, 256);
-  plan->off_merge = align_up(plan->off_items + sizeof(WorkItem) * items.size(), 256);
-  plan->upload_bytes = align_up(plan->off_merge + sizeof(MergeItem) * merges.size(), 256);
+  plan->off_merge = align_up(plan->off_items + sizeof(WorkItem) * n_slots, 256);
+  plan->upload_bytes = align_up(plan->off_merge + sizeof(MergeItem) * sc.merges.size(), 256);
   plan->off_partials = plan->upload_bytes;
   plan->total_bytes = align_up(plan->off_partials + sizeof(float) * partial_floats(D) * (size_t)n_partials, 256);
   if (plan->total_bytes == 0) plan->total_bytes = 256;
 
-  if (host_buf) {
-    unsigned char* h = static_cast<unsigned char*>(host_buf);
-    std::memset(h, 0, plan->upload_bytes);
-    if (n_seqs) std::memcpy(h + plan->off_seqs, seqs.data(), sizeof(SeqInfo) * (size_t)n_seqs);
-    WorkItem* wi = reinterpret_cast<WorkItem*>(h + plan->off_items);
-    for (size_t i = 0; i < items.size(); ++i) wi[i] = items[i].item;
-    if (!merges.empty()) std::memcpy(h + plan->off_merge, merges.data(), sizeof(MergeItem) * merges.size());
-  }
   return CRONUS_OK;
+}
+
+void write_plan(const Plan* plan, void* host_buf) {
+  // copies the work list that the last build_plan() of this thread left in its scratch
+  Scratch& sc = scratch();
+  const int32_t n_seqs = plan->n_seqs;
+  const size_t n_slots = (size_t)plan->n_items;
+  unsigned char* h = static_cast<unsigned char*>(host_buf);
+  if (n_seqs) std::memcpy(h + plan->off_seqs, sc.seqs.data(), sizeof(SeqInfo) * (size_t)n_seqs);
+  WorkItem* wi = reinterpret_cast<WorkItem*>(h + plan->off_items);
+  WorkItem idle{};
+  idle.wide = -1;
+  idle.partial = -1;
+  for (size_t i = 0; i < n_slots; ++i) {
+    const size_t k = i / kXcds, x = i % kXcds;
+    if (k < sc.queue[x].size()) {
+      const int32_t ref = sc.queue[x][k];
+      wi[i] = ref >= 0 ? sc.wide[(size_t)ref] : sc.narrow[(size_t)~ref];
+    } else {
+      wi[i] = idle;
+    }
+  }
+  if (!sc.merges.empty()) std::memcpy(h + plan->off_merge, sc.merges.data(), sizeof(MergeItem) * sc.merges.size());
 }
 
 }  // namespace cronus

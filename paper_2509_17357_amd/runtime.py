@@ -143,13 +143,14 @@ class DeviceIteration:
                                   self.block_tables, b.max_blocks, b.n_seqs, self.n_new_tokens, self._stream())
 
     def ensure_workspace(self):
-        need = B.cronus_attn_mixed_workspace_bytes(self.cache, self.batch.prefix_lens, self.batch.chunk_lens)
-        if need == 0:
-            raise RuntimeError("cronus_attn_mixed_workspace_bytes rejected the batch")
-        if self.workspace is None or self.workspace_bytes < need:
+        """Workspace for this batch's lengths (sized once: the lengths of a batch do not change)."""
+        if self.workspace is None:
+            need = B.cronus_attn_mixed_workspace_bytes(self.cache, self.batch.prefix_lens, self.batch.chunk_lens)
+            if need == 0:
+                raise RuntimeError("cronus_attn_mixed_workspace_bytes rejected the batch")
             self.workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
             self.workspace_bytes = need
-        return need
+        return self.workspace_bytes
 
     def attention(self):
         b = self.batch
