@@ -143,6 +143,19 @@ int cronus_attn_mixed_plan_stats(const cronus_kv_cache* cache, const int32_t* pr
                                  const int32_t* chunk_lens, int32_t n_seqs, int64_t* stats);
 
 /*
+ * cronus_attn_mixed_plan_items - the work list itself, for inspection and tests (host
+ * only, nothing is launched).  Writes up to `capacity` items, 12 int32 each, in grid
+ * order: seq, kv_head, head0, n_heads, q_tok0, n_tok, kv_begin, kv_end, partial, wide,
+ * 0, 0.  wide = 1: chunk tile (all keys [0, kv_end)); wide = 0: narrow item over keys
+ * [kv_begin, kv_end), partial >= 0 when its result is merged with other spans; wide = -1:
+ * idle slot.  Returns the number of items of the plan (which may exceed capacity), or
+ * a negative cronus_status on invalid arguments.  items may be NULL when capacity = 0.
+ */
+int64_t cronus_attn_mixed_plan_items(const cronus_kv_cache* cache, const int32_t* prefix_lens,
+                                     const int32_t* chunk_lens, int32_t n_seqs, int32_t* items,
+                                     int64_t capacity);
+
+/*
  * cronus_profile_events - measurement aid.  While both handles (hipEvent_t cast to
  * void*, created by the caller with timing enabled) are set, every cronus_attn_mixed
  * records `start` immediately before and `stop` immediately after its main attention

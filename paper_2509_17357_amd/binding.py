@@ -24,7 +24,7 @@ CRONUS_KV_BF16 = 0
 CRONUS_KV_FP8_E4M3 = 1
 
 EXPORTS = ("cronus_kv_append", "cronus_attn_mixed", "cronus_attn_mixed_workspace_bytes",
-           "cronus_attn_mixed_plan_stats", "cronus_profile_events", "cronus_status_string", "cronus_version")
+           "cronus_attn_mixed_plan_stats", "cronus_attn_mixed_plan_items", "cronus_profile_events", "cronus_status_string", "cronus_version")
 
 
 class cronus_kv_cache(ctypes.Structure):
@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.cronus_attn_mixed_workspace_bytes.restype = ctypes.c_size_t
         L.cronus_attn_mixed_plan_stats.argtypes = [cp, i32p, i32p, i32, ctypes.POINTER(ctypes.c_int64)]
         L.cronus_attn_mixed_plan_stats.restype = ctypes.c_int
+        L.cronus_attn_mixed_plan_items.argtypes = [cp, i32p, i32p, i32, i32p, ctypes.c_int64]
+        L.cronus_attn_mixed_plan_items.restype = ctypes.c_int64
         L.cronus_profile_events.argtypes = [vp, vp]
         L.cronus_profile_events.restype = None
         L.cronus_status_string.argtypes = [ctypes.c_int]
@@ -159,6 +161,22 @@ def cronus_attn_mixed_plan_stats(cache: cronus_kv_cache, prefix_lens, chunk_lens
     if rc != CRONUS_OK:
         raise CronusError(rc, "cronus_attn_mixed_plan_stats")
     return {"items": st[0], "wide_items": st[1], "partials": st[2], "merge_rows": st[3]}
+
+
+PLAN_ITEM_FIELDS = ("seq", "kv_head", "head0", "n_heads", "q_tok0", "n_tok", "kv_begin", "kv_end", "partial", "wide")
+
+
+def cronus_attn_mixed_plan_items(cache: cronus_kv_cache, prefix_lens, chunk_lens) -> np.ndarray:
+    """The work list as an int32 array [n_items, 12] (columns: PLAN_ITEM_FIELDS, then two zeros)."""
+    p, pp = _host_i32(prefix_lens)
+    c, cp = _host_i32(chunk_lens)
+    n = lib().cronus_attn_mixed_plan_items(ctypes.byref(cache), pp, cp, int(p.size), None, 0)
+    if n < 0:
+        raise CronusError(-n, "cronus_attn_mixed_plan_items")
+    out = np.zeros((max(n, 1), 12), dtype=np.int32)
+    lib().cronus_attn_mixed_plan_items(ctypes.byref(cache), pp, cp, int(p.size),
+                                       out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), int(n))
+    return out[:n]
 
 
 def cronus_attn_mixed(cache: cronus_kv_cache, q, out, prefix_lens, chunk_lens, block_tables,

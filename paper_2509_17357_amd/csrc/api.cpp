@@ -1,8 +1,11 @@
 // C ABI entry points (include/cronus.h): argument checks, plan upload, launches.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
+#include <cstring>
 #include <mutex>
+#include <vector>
 
 #include "cronus_internal.h"
 
@@ -123,6 +126,21 @@ int cronus_attn_mixed_plan_stats(const cronus_kv_cache* cache, const int32_t* pr
   stats[2] = plan.n_partials;
   stats[3] = plan.n_merge_rows;
   return CRONUS_OK;
+}
+
+int64_t cronus_attn_mixed_plan_items(const cronus_kv_cache* cache, const int32_t* prefix_lens,
+                                     const int32_t* chunk_lens, int32_t n_seqs, int32_t* items, int64_t capacity) {
+  if (int rc = check_shape(cache)) return -rc;
+  if (n_seqs < 0 || capacity < 0 || (n_seqs > 0 && (!prefix_lens || !chunk_lens)) || (capacity > 0 && !items))
+    return -CRONUS_ERR_INVALID_ARG;
+  Plan plan;
+  if (int rc = build_plan(cache, prefix_lens, chunk_lens, n_seqs, 0x7fffffff / kBlock, device_cus(), &plan)) return -rc;
+  std::vector<unsigned char> buf(plan.upload_bytes);
+  write_plan(&plan, buf.data());
+  static_assert(sizeof(WorkItem) == 12 * sizeof(int32_t), "plan item layout");
+  const int64_t n = std::min<int64_t>(capacity, plan.n_items);
+  if (n > 0) std::memcpy(items, buf.data() + plan.off_items, (size_t)n * sizeof(WorkItem));
+  return plan.n_items;
 }
 
 int cronus_attn_mixed(const cronus_kv_cache* cache, const void* q, void* out, const int32_t* prefix_lens,

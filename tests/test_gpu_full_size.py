@@ -1,0 +1,115 @@
+"""The five benchmark batches at FULL size, in the launch configuration bench.py times.
+Configs 1-3: every output row against the oracle.  Configs 4-5: the bulk of the K/V is
+drawn on the device; every chunk sequence and a seeded sample of decode sequences get
+host-drawn tensors and are checked row by row (config 5: a stratified sample of chunk
+rows: first and last tile, tile boundaries, and a uniform sample)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import cronus_oracle as orc
+from paper_2509_17357_amd import workloads as W
+from paper_2509_17357_amd.runtime import DeviceIteration, bf16_tensor_from_bits, bits_from_bf16_tensor
+
+import parity_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("cid", [2, 3])
+def test_full_batch_every_row(cid):
+    batch = W.draw_batch(cid)
+    it = DeviceIteration(batch, pool_fill=0x7FC1)
+    kv_bits = it.load_host_inputs()
+    it.setup_decode_context()
+    it.step()
+    torch.cuda.synchronize()
+    ref = U.oracle_attention(batch, bits_from_bf16_tensor(it.q), U.oracle_kv_values(batch, kv_bits), it.sm_scale)
+    rep = U.error_report(batch, bits_from_bf16_tensor(it.out), ref)
+    print(batch.name, rep)
+    U.assert_within_tolerance(rep)
+
+
+def _sampled_check(cid, n_decode_samples, chunk_row_sample):
+    batch = W.draw_batch(cid)
+    sh = batch.shape
+    it = DeviceIteration(batch)
+    it.load_device_inputs()
+    P, C = batch.prefix_lens.astype(np.int64), batch.chunk_lens.astype(np.int64)
+    dec = C == 1
+    rng = np.random.default_rng([batch.seed, 0x5A])
+    dec_ids = np.flatnonzero(dec)
+    sample = sorted(set(np.flatnonzero(~dec).tolist()) |
+                    set(rng.choice(dec_ids, size=min(n_decode_samples, dec_ids.size), replace=False).tolist()) |
+                    {int(dec_ids[np.argmax(P[dec_ids])]), int(dec_ids[np.argmin(P[dec_ids])])})
+    # overwrite the device-drawn rows of the sampled sequences with host-drawn ones
+    cu_prefix = np.concatenate([[0], np.cumsum(np.where(dec, 0, P))])
+    cu_ctx = np.concatenate([[0], np.cumsum(np.where(dec, P, 0))])
+    cu_new = batch.cu_q
+    q_bits_host = {}
+    kv_host = {}
+    for s in sample:
+        k, v = batch.gen_kv(s)
+        kv_host[s] = (k, v)
+        dst_k, dst_v, off = (it.ctx_k, it.ctx_v, cu_ctx[s]) if dec[s] else (it.prefix_k, it.prefix_v, cu_prefix[s])
+        dst_k[off:off + P[s]] = bf16_tensor_from_bits(k[:P[s]], it.device)
+        dst_v[off:off + P[s]] = bf16_tensor_from_bits(v[:P[s]], it.device)
+        it.new_k[cu_new[s]:cu_new[s + 1]] = bf16_tensor_from_bits(k[P[s]:], it.device)
+        it.new_v[cu_new[s]:cu_new[s + 1]] = bf16_tensor_from_bits(v[P[s]:], it.device)
+        q_bits_host[s] = bits_from_bf16_tensor(it.q[cu_new[s]:cu_new[s + 1]])
+    ks = vs = None
+    if it.fp8:
+        ks, vs = it.amax_scales()
+        it.set_fp8_scales(ks, vs)
+    it.setup_decode_context()
+    it.step()
+    torch.cuda.synchronize()
+    out = it.out
+    worst = 0.0
+    for s in sample:
+        k, v = kv_host[s]
+        sub = W.custom_batch(sh, [P[s]], [C[s]], seed=1)
+        (kf, vf), = U.oracle_kv_values(sub, [(k, v)], ks, vs)
+        q = orc.bf16_bits_to_f64(q_bits_host[s])
+        rows = np.arange(C[s]) if C[s] <= 512 else chunk_row_sample(int(C[s]), rng)
+        ref = orc.attn_rows(q, kf, vf, int(P[s]), it.sm_scale, rows=rows)
+        got = orc.bf16_bits_to_f64(bits_from_bf16_tensor(out[cu_new[s]:cu_new[s + 1]]))[rows]
+        assert not np.isnan(got).any(), s
+        err = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+        worst = max(worst, err)
+        assert err <= U.REL_L2_TOL, (s, err)
+        assert np.abs(got - ref).max() <= U.MAX_ABS_TOL, s
+        # scatter: the cache blocks of this sequence hold exactly its rows (bit-exact)
+        nb = int(batch.blocks_needed()[s])
+        ids = torch.from_numpy(batch.block_tables[s, :nb].astype(np.int64)).to(it.device)
+        per_blk = sh.n_kv_heads * 16 * sh.head_dim
+        kblk = it.k_pool.view(batch.num_blocks, per_blk)[ids].cpu().numpy()
+        vblk = it.v_pool.view(batch.num_blocks, per_blk)[ids].cpu().numpy()
+        view = (lambda a: a) if it.fp8 else (lambda a: a.view(np.uint16))
+        local = W.custom_batch(sh, [P[s]], [C[s]], seed=1)
+        local.block_tables = np.arange(nb, dtype=np.int32)[None, :]
+        local.num_blocks = nb
+        kp, vp = U.oracle_pools(local, [(k, v)], fill=0, k_scale=ks, v_scale=vs)
+        L = int(P[s] + C[s])
+        gk, gv = orc.kv_gather(view(kblk).reshape(-1), view(vblk).reshape(-1), np.arange(nb), L, sh.n_kv_heads, sh.head_dim)
+        ek, ev = orc.kv_gather(kp, vp, np.arange(nb), L, sh.n_kv_heads, sh.head_dim)
+        assert np.array_equal(gk, ek) and np.array_equal(gv, ev), s
+    print(batch.name, "sampled sequences", len(sample), "worst rel L2", worst)
+    # every output row of the batch is finite and of plausible size (properties that hold at any size)
+    o = out.float()
+    assert torch.isfinite(o).all()
+    assert float(o.abs().max()) < 1.0
+
+
+def test_config4_decode_heavy_sampled():
+    _sampled_check(4, 24, lambda c, rng: np.arange(c))
+
+
+def test_config5_fp8_long_context_sampled():
+    def rows(c, rng):
+        tile = 32  # tokens per wide tile at 8 heads per KV head
+        edges = np.concatenate([np.arange(0, tile), np.arange(c - tile, c),
+                                (np.arange(tile, c, 256)[:, None] + np.array([-1, 0])).ravel()])
+        uni = rng.choice(c, size=c // 64, replace=False)
+        return np.unique(np.clip(np.concatenate([edges, uni]), 0, c - 1))
+    _sampled_check(5, 12, rows)

@@ -1,0 +1,109 @@
+"""The host-side work decomposition (no GPU): every (sequence, q head, chunk token)
+must be covered by exactly one chain of items whose key ranges partition [0, prefix +
+token + 1) up to the tile's own causal end, spans must be aligned to what the kernel
+assumes, and idle slots must be inert."""
+import numpy as np
+import pytest
+
+from paper_2509_17357_amd import binding as B
+from paper_2509_17357_amd import workloads as W
+
+F = {n: i for i, n in enumerate(B.PLAN_ITEM_FIELDS)}
+
+
+def plan_for(shape, P, C):
+    c = B.make_cache(0, 0, 1 << 20, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                     B.CRONUS_KV_FP8_E4M3 if shape.kv_dtype == "fp8" else B.CRONUS_KV_BF16)
+    items = B.cronus_attn_mixed_plan_items(c, P, C)
+    stats = B.cronus_attn_mixed_plan_stats(c, P, C)
+    return items, stats
+
+
+def check_plan(shape, P, C):
+    P, C = np.asarray(P), np.asarray(C)
+    items, stats = plan_for(shape, P, C)
+    assert len(items) == stats["items"]
+    G = shape.n_q_heads // shape.n_kv_heads
+    real = items[items[:, F["wide"]] >= 0]
+    assert (items[items[:, F["wide"]] < 0][:, :8] == 0).all()  # idle slots carry nothing
+    assert (real[:, F["wide"]] == 1).sum() == stats["wide_items"]
+    # coverage[s][head, token] = list of (kv_begin, kv_end, partial)
+    cover = {}
+    for it in real:
+        s, kvh, h0, nh, t0, nt, kb, ke, part, wide = (int(x) for x in it[:10])
+        assert 0 <= s < len(P) and C[s] > 0 and 0 <= kvh < shape.n_kv_heads
+        assert h0 // G == kvh and (h0 + nh - 1) // G == kvh and nh >= 1   # heads of one KV head
+        assert 0 <= t0 and nt >= 1 and t0 + nt <= C[s]
+        assert nt * nh <= (256 if wide else 32)
+        if wide:
+            assert kb == 0 and ke == P[s] + t0 + nt and part == -1
+        else:
+            assert kb % 256 == 0 and kb < ke <= P[s] + t0 + nt
+        for h in range(h0, h0 + nh):
+            for t in range(t0, t0 + nt):
+                cover.setdefault((s, h, t), []).append((kb, ke, part, t0 + nt))
+    n_partial = 0
+    for s in range(len(P)):
+        for h in range(shape.n_q_heads):
+            for t in range(int(C[s])):
+                spans = sorted(cover.pop((s, h, t)))
+                tile_end = spans[0][3]
+                assert spans[0][0] == 0 and spans[-1][1] == P[s] + tile_end   # whole visible range of the tile
+                for a, b in zip(spans, spans[1:]):
+                    assert a[1] == b[0]                                        # no gap, no overlap
+                if len(spans) > 1:
+                    assert all(sp[2] >= 0 for sp in spans)                     # merged through partial slots
+                else:
+                    assert spans[0][2] == -1
+    assert not cover
+    parts = real[real[:, F["partial"]] >= 0][:, F["partial"]]
+    assert sorted(parts.tolist()) == list(range(stats["partials"]))          # each slot written once
+    return items, stats
+
+
+@pytest.mark.parametrize("cid", [1, 2, 3, 4])
+def test_plan_covers_benchmark_batches(cid):
+    b = W.draw_batch(cid, scale=1.0 if cid in (1, 2) else 0.25)
+    check_plan(b.shape, b.prefix_lens, b.chunk_lens)
+
+
+def test_plan_edge_cases():
+    sh = W.SHAPE_8B
+    check_plan(sh, [0], [1])                       # a single key
+    check_plan(sh, [0, 5, 0], [0, 0, 3])           # empty sequences are skipped
+    check_plan(sh, [100000], [1])                  # long decode: many spans
+    check_plan(sh, [7], [65])                      # one wide tile and a one-token narrow tail
+    check_plan(W.HeadShape(28, 4, 128), [10, 129, 0], [50, 1, 260])   # G = 7
+    check_plan(W.HeadShape(64, 1, 128), [33], [40])                    # G = 64 > 32: two head groups
+    check_plan(W.HeadShape(4, 4, 64), [5, 0, 63], [40, 200, 1])        # MHA
+    items, stats = plan_for(sh, [], [])
+    assert stats["items"] == 0 and len(items) == 0
+
+
+def test_plan_queues_follow_xcd_order():
+    """Work-group i runs on XCD i % 8: the wide tiles of one (sequence, KV head) sit in few
+    queues, and within a queue they come longest first."""
+    b = W.draw_batch(3)
+    items, _ = plan_for(b.shape, b.prefix_lens, b.chunk_lens)
+    wide = [(i % 8, it) for i, it in enumerate(items) if it[F["wide"]] == 1]
+    queues_of = {}
+    for x, it in wide:
+        queues_of.setdefault((int(it[F["seq"]]), int(it[F["kv_head"]])), set()).add(x)
+    assert max(len(v) for v in queues_of.values()) <= 2
+    for x in range(8):
+        last = {}
+        for xx, it in wide:
+            if xx != x:
+                continue
+            key = (int(it[F["seq"]]), int(it[F["kv_head"]]))
+            if key in last:
+                assert it[F["kv_end"]] <= last[key]
+            last[key] = int(it[F["kv_end"]])
+    # the eight queues carry similar amounts of work
+    load = np.zeros(8)
+    for i, it in enumerate(items):
+        if it[F["wide"]] == 1:
+            load[i % 8] += 2.0 * it[F["kv_end"]]
+        elif it[F["wide"]] == 0:
+            load[i % 8] += 0.5 * (it[F["kv_end"]] - it[F["kv_begin"]])
+    assert load.max() <= 1.1 * load.mean()
