@@ -22,6 +22,9 @@
 
 #include "cronus_internal.h"
 
+#ifndef CRONUS_SPLIT_ISSUE
+#define CRONUS_SPLIT_ISSUE 1
+#endif
 #ifndef CRONUS_HINT
 #define CRONUS_HINT 7  // VALU instructions issued per MFMA in the interleaved block
 #endif
@@ -37,6 +40,7 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
+constexpr float kLazyLog2 = 8.0f;  // slack of the running reference of the online softmax, in bits
 constexpr float kNeg = -1.0e30f;  // initial running maximum: finite, so that differences of maxima stay finite
 
 struct AttnParams {
@@ -133,8 +137,12 @@ __device__ __forceinline__ void softmax_max_part(f32x16& s, bool need_mask, int 
 #pragma unroll
   for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i]);
   mx = pair_max(mx);
-  const float m_new = fmaxf(m, mx);
-  if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {  // wave-uniform: some row's maximum grew
+  // The reference m of a row only has to bound its scores loosely: numerators up to
+  // 2^kLazyLog2 keep their relative precision in bf16 and their sums stay far from the
+  // fp32 range, so O and l are rescaled only when some row's maximum outgrew its
+  // reference by more than that (wave-uniform branch; every row then takes its true maximum).
+  if (__builtin_amdgcn_ballot_w64((mx - m) * c > kLazyLog2) != 0) {
+    const float m_new = fmaxf(m, mx);
     const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
     l *= alpha;
 #pragma unroll
@@ -352,11 +360,25 @@ typedef __attribute__((address_space(3))) unsigned char lds_byte;
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
-  static_assert(N == 0 || N == 2 || N == 4 || N == 8, "counts used by the DMA pipelines");
-  if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  if constexpr (N == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-  if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-  if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"i"(N) : "memory");
+}
+
+#ifndef CRONUS_DMA_DWORD
+#define CRONUS_DMA_DWORD 0
+#endif
+// Copy 1 KiB, global -> LDS, by one wave: g and dst are the wave's bases (no lane term).
+constexpr int kDmaPerKiB = CRONUS_DMA_DWORD ? 4 : 1;
+__device__ __forceinline__ void dma_1k(const unsigned char* g, lds_byte* dst, int lane) {
+#if CRONUS_DMA_DWORD
+  const unsigned char* gl = g + lane * 4;
+  __builtin_amdgcn_global_load_lds(gl, dst, 4, 0, 0);
+  __builtin_amdgcn_global_load_lds(gl, dst, 4, 256, 0);
+  __builtin_amdgcn_global_load_lds(gl, dst, 4, 512, 0);
+  __builtin_amdgcn_global_load_lds(gl, dst, 4, 768, 0);
+#else
+  __builtin_amdgcn_global_load_lds(g + lane * 16, dst, 16, 0, 0);
+#endif
 }
 
 // LDS reads of data that arrived by global_load_lds are written as asm, so that the
@@ -385,6 +407,42 @@ __device__ __forceinline__ void lds_read8(u32x4 (&x)[8], unsigned addr) {
       : "memory");
 }
 
+// Split form for the steady-state loop: issue the reads, do independent work, then land
+// them.  `lds_land` names the destination registers as in-out operands of the wait, so
+// every later use of them depends on the wait; N = LDS reads issued after these that may
+// still be outstanding (LDS reads return in order).
+template <int O0, int O1, int O2, int O3>
+__device__ __forceinline__ void lds_issue4(u32x4 (&x)[4], unsigned addr) {
+  asm volatile(
+      "ds_read_b128 %0, %4 offset:%5\n\tds_read_b128 %1, %4 offset:%6\n\t"
+      "ds_read_b128 %2, %4 offset:%7\n\tds_read_b128 %3, %4 offset:%8"
+      : "=&v"(x[0]), "=&v"(x[1]), "=&v"(x[2]), "=&v"(x[3])
+      : "v"(addr), "i"(O0), "i"(O1), "i"(O2), "i"(O3)
+      : "memory");
+}
+template <int O0, int O1, int O2, int O3, int O4, int O5, int O6, int O7>
+__device__ __forceinline__ void lds_issue8(u32x4 (&x)[8], unsigned addr) {
+  asm volatile(
+      "ds_read_b128 %0, %8 offset:%9\n\tds_read_b128 %1, %8 offset:%10\n\t"
+      "ds_read_b128 %2, %8 offset:%11\n\tds_read_b128 %3, %8 offset:%12\n\t"
+      "ds_read_b128 %4, %8 offset:%13\n\tds_read_b128 %5, %8 offset:%14\n\t"
+      "ds_read_b128 %6, %8 offset:%15\n\tds_read_b128 %7, %8 offset:%16"
+      : "=&v"(x[0]), "=&v"(x[1]), "=&v"(x[2]), "=&v"(x[3]), "=&v"(x[4]), "=&v"(x[5]), "=&v"(x[6]), "=&v"(x[7])
+      : "v"(addr), "i"(O0), "i"(O1), "i"(O2), "i"(O3), "i"(O4), "i"(O5), "i"(O6), "i"(O7)
+      : "memory");
+}
+template <int N>
+__device__ __forceinline__ void lds_land(u32x4 (&x)[4]) {
+  asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]) : "i"(N) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void lds_land(u32x4 (&x)[8]) {
+  asm volatile("s_waitcnt lgkmcnt(%8)"
+               : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7])
+               : "i"(N)
+               : "memory");
+}
+
 // Schedule per wave (n = number of 32-key sub-tiles, S(u) = K(u) Q^T, P(u) = softmax
 // numerators), software-pipelined by one sub-tile so that the MFMA pipe has the S(u+1)
 // products to work on while the VALU computes the softmax of S(u):
@@ -403,7 +461,7 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
   constexpr int kStages = 4, kAhead = kStages - 1;
   constexpr int UPW = D / 64;             // 1-KiB units of K (and of V) each wave fetches per tile
   constexpr int UPB = BLK_LDS / 1024;     // units per block
-  constexpr int NI = 2 * UPW;             // DMA instructions per wave per tile
+  constexpr int NI = 2 * UPW * kDmaPerKiB;  // DMA instructions per wave per tile
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, half = lane >> 5, c32 = lane & 31;
@@ -456,13 +514,27 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
       asm volatile("" : "+v"(bt_reg));
     }
     const long long b = __builtin_amdgcn_readlane(bt_reg, j & 63);
-    const long long goff = (b * p.n_kv_heads + it.kv_head) * head_stride + part_w * 1024 + lane * 16;
+    const long long goff = (b * p.n_kv_heads + it.kv_head) * head_stride + part_w * 1024;
     lds_byte* dst = lds0 + (j % kStages) * STAGE + blk_w * BLK_LDS + part_w * 1024;
 #pragma unroll
     for (int x = 0; x < UPW; ++x) {
-      __builtin_amdgcn_global_load_lds(p.k_pool + goff + x * 1024, dst + x * 1024, 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(p.v_pool + goff + x * 1024, dst + KT_BYTES + x * 1024, 16, 0, 0);
+      dma_1k(p.k_pool + goff + x * 1024, dst + x * 1024, lane);
+      dma_1k(p.v_pool + goff + x * 1024, dst + KT_BYTES + x * 1024, lane);
     }
+  };
+  // one of the NI instructions of tile j (q = 2 x + is_v), for spreading a tile's fetch
+  // over the two sub-tile steps of a period
+  auto issue_part = [&](int j, int q) {
+    if (q == 0 && (j & 63) == 0) {
+      bt_reg = bt[min(4 * (j + lane) + blk_w, last_blk)];
+      asm volatile("" : "+v"(bt_reg));
+    }
+    const long long b = __builtin_amdgcn_readlane(bt_reg, j & 63);
+    const long long goff = (b * p.n_kv_heads + it.kv_head) * head_stride + part_w * 1024;
+    lds_byte* dst = lds0 + (j % kStages) * STAGE + blk_w * BLK_LDS + part_w * 1024;
+    const int x = q >> 1;
+    if (q & 1) dma_1k(p.v_pool + goff + x * 1024, dst + KT_BYTES + x * 1024, lane);
+    else dma_1k(p.k_pool + goff + x * 1024, dst + x * 1024, lane);
   };
 
   // ---- LDS operand reads (byte addresses)
@@ -480,6 +552,17 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
     if constexpr (NSTEP == 8)
       lds_read8<0, 512, 1024, 1536, BLK_LDS, BLK_LDS + 512, BLK_LDS + 1024, BLK_LDS + 1536>(va, a);
     else lds_read4<0, 512, BLK_LDS, BLK_LDS + 512>(va[0], va[1], va[2], va[3], a);
+  };
+  auto issue_k = [&](int u) {
+    const unsigned a = k_lane + ((u >> 1) % kStages) * STAGE + (u & 1) * 2 * BLK_LDS;
+    if constexpr (NSTEP == 8) lds_issue8<0, 512, 1024, 1536, 2048, 2560, 3072, 3584>(ka, a);
+    else lds_issue4<0, 512, 1024, 1536>(ka, a);
+  };
+  auto issue_v = [&](int u) {
+    const unsigned a = v_lane + ((u >> 1) % kStages) * STAGE + (u & 1) * 2 * BLK_LDS;
+    if constexpr (NSTEP == 8)
+      lds_issue8<0, 512, 1024, 1536, BLK_LDS, BLK_LDS + 512, BLK_LDS + 1024, BLK_LDS + 1536>(va, a);
+    else lds_issue4<0, 512, BLK_LDS, BLK_LDS + 512>(va, a);
   };
   auto active = [&](int u) { return 32 * u <= wave_max_limit; };
 
@@ -541,7 +624,9 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
   // block and are interleaved: the wave keeps issuing VALU work while each MFMA of the
   // dependent chain is in the pipe.
   auto fast_step = [&](int u, f32x16& s_cur, f32x16& s_nxt, bool opens_tile) {
+    issue_v(u);              // lands during the block below
     softmax_max_part<NDB>(s_cur, false, 32 * u, half, limit, c, m, l, o);
+    lds_land<NSTEP>(ka);     // K(u+1), issued before the previous step's O products
     qk(s_nxt);
     softmax_exp_part(s_cur, c, m, l, pp);
 #if CRONUS_HINT
@@ -551,13 +636,18 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
       __builtin_amdgcn_sched_group_barrier(0x402, CRONUS_HINT, 0);
     }
 #endif
-    read_v(u);
+    const int jn = (u >> 1) + kAhead;
     if (opens_tile) {
       wait_vmcnt<NI>();
       __builtin_amdgcn_s_barrier();
-      issue_tile((u >> 1) + kAhead);
+      issue_part(jn, 0);
+      issue_part(jn, 1);
+    } else if constexpr (UPW > 1) {
+      issue_part(jn, 2);
+      issue_part(jn, 3);
     }
-    read_k(u + 2);
+    issue_k(u + 2);          // lands during the O products
+    lds_land<NSTEP>(va);     // V(u)
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -572,6 +662,7 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
     fast_step(u, s_even, s_odd, true);
     fast_step(u + 1, s_odd, s_even, false);
   }
+  lds_land<0>(ka);  // the steps below expect K(u+1) in registers
   for (; u < n_sub; u += 2) {
     step(u, s_even, s_odd, true);
     if (u + 1 < n_sub) step(u + 1, s_odd, s_even, false);
