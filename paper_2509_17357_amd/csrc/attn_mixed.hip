@@ -123,7 +123,7 @@ __device__ __forceinline__ u32x4 to_bf16_chunk(typename RawChunk<FP8>::type c) {
 // Returns the two P^T operands (keys 0-15 and 16-31 of the sub-tile).
 // First part: causal mask, running maximum (rescales O and l when some row's maximum
 // grew).  Second part: numerators, their row sum, and the bf16 P^T operands.
-template <int NDB>
+template <int NDB, bool FORCE = false>
 __device__ __forceinline__ void softmax_max_part(f32x16& s, bool need_mask, int sub_base, int half, int limit,
                                                  float c, float& m, float& l, f32x16 (&o)[NDB]) {
   if (need_mask) {
@@ -141,7 +141,7 @@ __device__ __forceinline__ void softmax_max_part(f32x16& s, bool need_mask, int 
   // 2^kLazyLog2 keep their relative precision in bf16 and their sums stay far from the
   // fp32 range, so O and l are rescaled only when some row's maximum outgrew its
   // reference by more than that (wave-uniform branch; every row then takes its true maximum).
-  if (__builtin_amdgcn_ballot_w64((mx - m) * c > kLazyLog2) != 0) {
+  if (FORCE || __builtin_amdgcn_ballot_w64((mx - m) * c > kLazyLog2) != 0) {
     const float m_new = fmaxf(m, mx);
     const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
     l *= alpha;
@@ -152,8 +152,13 @@ __device__ __forceinline__ void softmax_max_part(f32x16& s, bool need_mask, int 
     m = m_new;
   }
 }
-__device__ __forceinline__ void softmax_exp_part(const f32x16& s, float c, float m, float& l, u32x4 (&p)[2]) {
+// Numerators 2^(c (s - m)) as bf16 P^T operands, and this lane's sum of them.  The sum
+// adds the ROUNDED numerators (one dot product with (1, 1) per packed pair), so l
+// normalises exactly the weights that multiply V.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float softmax_exp_part(const f32x16& s, float c, float m, u32x4 (&p)[2]) {
   const float mc = m * c;
+  const bf16x2_t ones = __builtin_bit_cast(bf16x2_t, 0x3f803f80u);
   float sum = 0.f;
 #pragma unroll
   for (int t = 0; t < 2; ++t)
@@ -161,17 +166,22 @@ __device__ __forceinline__ void softmax_exp_part(const f32x16& s, float c, float
     for (int w = 0; w < 4; ++w) {
       const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * t + 2 * w], c, -mc));
       const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * t + 2 * w + 1], c, -mc));
-      sum += e0 + e1;
-      p[t][w] = pack_bf16(e0, e1);
+      const f32x2 e = {e0, e1};
+      const bf16x2_t pk = __builtin_convertvector(e, bf16x2_t);
+      p[t][w] = __builtin_bit_cast(unsigned int, pk);
+      sum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, sum, false);
     }
-  l += sum;
+  return sum;
 }
 template <int NDB>
 __device__ __forceinline__ void softmax_tile(f32x16& s, bool need_mask, int sub_base, int half, int limit,
                                              float c, float& m, float& l, f32x16 (&o)[NDB], u32x4 (&p)[2]) {
   softmax_max_part<NDB>(s, need_mask, sub_base, half, limit, c, m, l, o);
-  softmax_exp_part(s, c, m, l, p);
+  l += softmax_exp_part(s, c, m, p);
 }
+// A lane's 16 numerators are each at most 2^kLazyLog2 when its reference is fresh enough.
+constexpr float kTileSumLimit = 16.0f * 256.0f;
+static_assert(kLazyLog2 == 8.0f, "kTileSumLimit = 16 * 2^kLazyLog2");
 
 // Store one lane's share of a finished row: dims 32*db + 16*j + 8*half + 0..7.
 template <int NDB>
@@ -625,10 +635,12 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
   // dependent chain is in the pipe.
   auto fast_step = [&](int u, f32x16& s_cur, f32x16& s_nxt, bool opens_tile) {
     issue_v(u);              // lands during the block below
-    softmax_max_part<NDB>(s_cur, false, 32 * u, half, limit, c, m, l, o);
     lds_land<NSTEP>(ka);     // K(u+1), issued before the previous step's O products
     qk(s_nxt);
-    softmax_exp_part(s_cur, c, m, l, pp);
+    // optimistic: numerators against the reference as it is; the row maxima are looked
+    // at only if some lane's sum shows that a score outgrew the reference (or it is the
+    // first sub-tile, whose reference is kNeg and whose numerators overflow)
+    float tile_sum = softmax_exp_part(s_cur, c, m, pp);
 #if CRONUS_HINT
 #pragma unroll
     for (int i = 0; i < NSTEP; ++i) {
@@ -636,6 +648,11 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
       __builtin_amdgcn_sched_group_barrier(0x402, CRONUS_HINT, 0);
     }
 #endif
+    if (__builtin_amdgcn_ballot_w64(!(tile_sum <= kTileSumLimit)) != 0) {
+      softmax_max_part<NDB, true>(s_cur, false, 32 * u, half, limit, c, m, l, o);
+      tile_sum = softmax_exp_part(s_cur, c, m, pp);
+    }
+    l += tile_sum;
     const int jn = (u >> 1) + kAhead;
     if (opens_tile) {
       wait_vmcnt<NI>();
