@@ -109,11 +109,13 @@ def time_workload(name, steps, warmup, trial=0):
     return res, batch
 
 
-def cpu_baseline(batch, budget_s=12.0):
+def cpu_baseline(batch, budget_s=12.0, min_s=10.0):
     """The fp64 oracle, untuned, on a bounded stratified sample of the same batch:
     chunk sequences and decode sequences are sampled separately (whole sequences, in
     batch order, until each group has used its share of the time budget) and each
-    group's time is scaled to the whole batch by its visible (query, key) pairs."""
+    group's time is scaled to the whole batch by its visible (query, key) pairs.  A batch
+    the oracle finishes sooner is passed over again until about min_s seconds of CPU work
+    have been timed, so that the figure is not a cold first call."""
     import threadpoolctl
 
     from oracle import cronus_oracle as orc
@@ -125,31 +127,40 @@ def cpu_baseline(batch, budget_s=12.0):
     q_bits = batch.gen_q()
     pairs = C * P + C * (C + 1) // 2
     groups = {"chunk": [s for s in range(batch.n_seqs) if C[s] > 1], "decode": [s for s in range(batch.n_seqs) if C[s] == 1]}
-    est_full_s, t_total, seqs_done, pairs_done, rows_done = 0.0, 0.0, 0, 0, 0
-    for name, ids in groups.items():
-        if not ids:
-            continue
-        t_used, done = 0.0, 0
-        for s in ids:
-            if t_used > budget_s:
-                break
-            k_bits, v_bits = batch.gen_kv(s)
-            q = orc.bf16_bits_to_f64(q_bits[cu[s]:cu[s + 1]])
-            k, v = orc.bf16_bits_to_f64(k_bits), orc.bf16_bits_to_f64(v_bits)
-            t0 = time.perf_counter()
-            orc.attn_rows(q, k, v, int(P[s]), sm_scale)
-            t_used += time.perf_counter() - t0
-            done += int(pairs[s])
-            seqs_done += 1
-            rows_done += int(C[s])
-        est_full_s += t_used * int(pairs[ids].sum()) / max(done, 1)
-        t_total += t_used
-        pairs_done += done
+    t_used = {g: 0.0 for g in groups}
+    done = {g: 0 for g in groups}
+    seqs_seen, rows_seen = set(), 0
+    passes, t_total = 0, 0.0
+    inputs = {}
+    while passes == 0 or (t_total < min_s and passes < 64):
+        passes += 1
+        for name, ids in groups.items():
+            t_pass = 0.0
+            for s in ids:
+                if t_pass > budget_s:
+                    break
+                if s not in inputs:
+                    k_bits, v_bits = batch.gen_kv(s)
+                    inputs[s] = (orc.bf16_bits_to_f64(q_bits[cu[s]:cu[s + 1]]), orc.bf16_bits_to_f64(k_bits),
+                                 orc.bf16_bits_to_f64(v_bits))
+                q, k, v = inputs[s]
+                t0 = time.perf_counter()
+                orc.attn_rows(q, k, v, int(P[s]), sm_scale)
+                dt = time.perf_counter() - t0
+                t_pass += dt
+                done[name] += int(pairs[s])
+                if s not in seqs_seen:
+                    seqs_seen.add(s)
+                    rows_seen += int(C[s])
+            t_used[name] += t_pass
+            t_total += t_pass
+    est_full_s = sum(t_used[g] * int(pairs[ids].sum()) / max(done[g], 1) for g, ids in groups.items() if ids)
+    pairs_done = sum(done.values())
     threads = max((i.get("num_threads", 1) for i in threadpoolctl.threadpool_info()), default=1)
     return {"value": batch.total_q / est_full_s, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{rows_done} query rows of {seqs_done} whole sequences ({pairs_done} of {int(pairs.sum())} "
-                      f"visible (query,key) pairs per head) in {t_total:.2f} s; chunk and decode groups scaled "
-                      f"separately to the whole batch by pairs",
+            "sample": f"{rows_seen} query rows of {len(seqs_seen)} whole sequences, {passes} pass(es): {pairs_done} "
+                      f"visible (query,key) pairs per head timed in {t_total:.2f} s (the batch has {int(pairs.sum())}); "
+                      f"chunk and decode groups scaled separately to the whole batch by pairs",
             "oracle_seconds_full_batch_extrapolated": est_full_s,
             "oracle_gflops": 4 * sh.head_dim * sh.n_q_heads * pairs_done / max(t_total, 1e-9) / 1e9}
 
