@@ -156,6 +156,67 @@ int64_t cronus_attn_mixed_plan_items(const cronus_kv_cache* cache, const int32_t
                                      int64_t capacity);
 
 /*
+ * cronus_kv_gather - the inverse of cronus_kv_append: export logical positions
+ * [start_pos[s], start_pos[s] + n) of each sequence from its paged blocks into
+ * contiguous rows (section 4.2: the partially prefilled prefix leaves the instance that
+ * computed it as one contiguous KV cache buffer; the receiving side stores it with
+ * cronus_kv_append).  Row r of sequence s (n = cu_tokens[s+1]-cu_tokens[s] rows) is
+ * destination row cu_tokens[s]+r and comes from block
+ * block_tables[s*max_blocks_per_seq + p/16], slot p%16, p = start_pos[s]+r.
+ *
+ *   k_dst, v_dst : device, [n_tokens][Hkv][D]; bf16 for a bf16 cache (bit-exact copy),
+ *                  raw e4m3 codes (1 byte per element) for an fp8 cache: codes are
+ *                  exported as stored, the scales travel separately
+ *   cu_tokens, start_pos, block_tables : device, as for cronus_kv_append
+ * Every destination row of the call is written in full; nothing else is.
+ * Errors: INVALID_ARG (null pointer, negative count), UNSUPPORTED (shape/dtype), HIP.
+ */
+int cronus_kv_gather(const cronus_kv_cache* cache, void* k_dst, void* v_dst,
+                     const int32_t* cu_tokens, const int32_t* start_pos,
+                     const int32_t* block_tables, int32_t max_blocks_per_seq, int32_t n_seqs,
+                     int32_t n_tokens, void* hip_stream);
+
+/*
+ * Execution-time models that the balancer uses (section 4.4): a partial prefill of L
+ * tokens on the partial prefill instance takes k_p * L + b_p (Eq. 2); one chunked
+ * prefill iteration whose prefill request has context L_ctx next to decode requests of
+ * total context L_ctxd takes k_ctxp * L_ctx + k_ctxd * L_ctxd + b_c (Eq. 3).  All times
+ * in one unit of the caller's choice.
+ */
+typedef struct cronus_balancer_model {
+  double k_p, b_p;            /* Eq. 2 */
+  double k_ctxp, k_ctxd, b_c; /* Eq. 3 */
+  int32_t block_size;         /* N_size: tokens per KV block of the chunked prefill instance */
+  int32_t batch_tokens;       /* B: most tokens batched into one iteration                   */
+  int32_t n_candidates;       /* candidate split points, evenly spaced; 512 in Algorithm 1   */
+} cronus_balancer_model;
+
+/*
+ * cronus_balancer_split - partial prefill length of one request (Algorithm 1 of the
+ * appendix, with Eq. 1-3).  Host function; touches no device.
+ *   l_in   : prompt length in tokens (> 0)
+ *   n_d    : decode requests on the chunked prefill instance (0 <= n_d < batch_tokens);
+ *            each iteration has n_p = batch_tokens - n_d prefill tokens
+ *   l_ctxd : sum of those requests' context lengths (>= 0)
+ *   n_free : free KV blocks of the chunked prefill instance (>= 0)
+ *   l_p    : host, out; the chosen length, 1 <= *l_p <= l_in.  l_in itself when the
+ *            prompt's ceil(l_in / N_size) blocks do not fit into n_free (the whole
+ *            prompt is then prefilled on the partial prefill instance)
+ *   t_prefill, t_chunked : host, out, may be NULL; the two modelled times for the
+ *            returned length (on the capacity fallback l_p = l_in and t_chunked = 0)
+ * Candidate j = 1..n_candidates is L_p = ceil(j * l_in / n_candidates); with
+ * L_c = l_in - L_p, N_iter = ceil(L_c / n_p), L_last = L_p + floor(L_c / n_p) * n_p the
+ * chunked time is N_iter * (k_ctxp * (l_in + L_last) / 2 + k_ctxd * l_ctxd + b_c), as
+ * printed in Algorithm 1; the first candidate with the smallest |T_prefill - T_chunked|
+ * wins.  Arithmetic is IEEE double without contraction, integers converted exactly.
+ * Errors: INVALID_ARG (null model or l_p, values outside the ranges above, products
+ * that would leave the exactly representable integer range).
+ */
+int cronus_balancer_split(const cronus_balancer_model* model, int64_t l_in, int64_t n_d,
+                          int64_t l_ctxd, int64_t n_free, int64_t* l_p, double* t_prefill,
+                          double* t_chunked);
+
+/*
  * cronus_profile_events - measurement aid.  While both handles (hipEvent_t cast to
  * void*, created by the caller with timing enabled) are set, every cronus_attn_mixed
  * records `start` immediately before and `stop` immediately after its main attention

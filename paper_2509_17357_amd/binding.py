@@ -23,8 +23,9 @@ CRONUS_ERR_HIP = 4
 CRONUS_KV_BF16 = 0
 CRONUS_KV_FP8_E4M3 = 1
 
-EXPORTS = ("cronus_kv_append", "cronus_attn_mixed", "cronus_attn_mixed_workspace_bytes",
-           "cronus_attn_mixed_plan_stats", "cronus_attn_mixed_plan_items", "cronus_profile_events", "cronus_status_string", "cronus_version")
+EXPORTS = ("cronus_kv_append", "cronus_kv_gather", "cronus_attn_mixed", "cronus_attn_mixed_workspace_bytes",
+           "cronus_attn_mixed_plan_stats", "cronus_attn_mixed_plan_items", "cronus_balancer_split",
+           "cronus_profile_events", "cronus_status_string", "cronus_version")
 
 
 class cronus_kv_cache(ctypes.Structure):
@@ -34,6 +35,12 @@ class cronus_kv_cache(ctypes.Structure):
                 ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("block_size", ctypes.c_int32),
                 ("kv_dtype", ctypes.c_int32)]
+
+
+class cronus_balancer_model(ctypes.Structure):
+    _fields_ = [("k_p", ctypes.c_double), ("b_p", ctypes.c_double),
+                ("k_ctxp", ctypes.c_double), ("k_ctxd", ctypes.c_double), ("b_c", ctypes.c_double),
+                ("block_size", ctypes.c_int32), ("batch_tokens", ctypes.c_int32), ("n_candidates", ctypes.c_int32)]
 
 
 class CronusError(RuntimeError):
@@ -57,6 +64,12 @@ def lib() -> ctypes.CDLL:
         cp = ctypes.POINTER(cronus_kv_cache)
         L.cronus_kv_append.argtypes = [cp, vp, vp, vp, vp, vp, i32, i32, i32, vp]
         L.cronus_kv_append.restype = ctypes.c_int
+        L.cronus_kv_gather.argtypes = [cp, vp, vp, vp, vp, vp, i32, i32, i32, vp]
+        L.cronus_kv_gather.restype = ctypes.c_int
+        i64, f64p = ctypes.c_int64, ctypes.POINTER(ctypes.c_double)
+        L.cronus_balancer_split.argtypes = [ctypes.POINTER(cronus_balancer_model), i64, i64, i64, i64,
+                                            ctypes.POINTER(ctypes.c_int64), f64p, f64p]
+        L.cronus_balancer_split.restype = ctypes.c_int
         L.cronus_attn_mixed.argtypes = [cp, vp, vp, i32p, i32p, vp, i32, i32, ctypes.c_float, vp, ctypes.c_size_t, vp]
         L.cronus_attn_mixed.restype = ctypes.c_int
         L.cronus_attn_mixed_workspace_bytes.argtypes = [cp, i32p, i32p, i32]
@@ -145,6 +158,33 @@ def cronus_kv_append(cache: cronus_kv_cache, k_src, v_src, cu_tokens, start_pos,
     if check and rc != CRONUS_OK:
         raise CronusError(rc, "cronus_kv_append")
     return rc
+
+
+def cronus_kv_gather(cache: cronus_kv_cache, k_dst, v_dst, cu_tokens, start_pos, block_tables,
+                     max_blocks_per_seq: int, n_seqs: int, n_tokens: int, stream: int = 0, check=True) -> int:
+    """k_dst, v_dst, cu_tokens, start_pos, block_tables: device tensors (or addresses)."""
+    rc = lib().cronus_kv_gather(ctypes.byref(cache), _ptr(k_dst), _ptr(v_dst), _ptr(cu_tokens), _ptr(start_pos),
+                                _ptr(block_tables), int(max_blocks_per_seq), int(n_seqs), int(n_tokens),
+                                ctypes.c_void_p(stream))
+    if check and rc != CRONUS_OK:
+        raise CronusError(rc, "cronus_kv_gather")
+    return rc
+
+
+def cronus_balancer_split(l_in: int, n_d: int, l_ctxd: int, n_free: int, k_p: float, b_p: float, k_ctxp: float,
+                          k_ctxd: float, b_c: float, n_size: int = 16, batch_tokens: int = 512,
+                          n_candidates: int = 512, with_times: bool = False, check=True):
+    """Partial prefill length (and, with_times, the two modelled times of that split)."""
+    model = cronus_balancer_model(k_p, b_p, k_ctxp, k_ctxd, b_c, n_size, batch_tokens, n_candidates)
+    l_p = ctypes.c_int64(-1)
+    tp, tc = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    rc = lib().cronus_balancer_split(ctypes.byref(model), int(l_in), int(n_d), int(l_ctxd), int(n_free),
+                                     ctypes.byref(l_p), ctypes.byref(tp), ctypes.byref(tc))
+    if rc != CRONUS_OK:
+        if check:
+            raise CronusError(rc, "cronus_balancer_split")
+        return rc
+    return (l_p.value, tp.value, tc.value) if with_times else l_p.value
 
 
 def cronus_attn_mixed_workspace_bytes(cache: cronus_kv_cache, prefix_lens, chunk_lens) -> int:

@@ -106,6 +106,17 @@ int cronus_kv_append(const cronus_kv_cache* cache, const void* k_src, const void
                           n_tokens, hip_stream);
 }
 
+int cronus_kv_gather(const cronus_kv_cache* cache, void* k_dst, void* v_dst, const int32_t* cu_tokens,
+                     const int32_t* start_pos, const int32_t* block_tables, int32_t max_blocks_per_seq,
+                     int32_t n_seqs, int32_t n_tokens, void* hip_stream) {
+  if (int rc = check_cache(cache)) return rc;
+  if (n_seqs < 0 || n_tokens < 0 || max_blocks_per_seq <= 0) return CRONUS_ERR_INVALID_ARG;
+  if (n_tokens == 0 || n_seqs == 0) return CRONUS_OK;
+  if (!k_dst || !v_dst || !cu_tokens || !start_pos || !block_tables) return CRONUS_ERR_INVALID_ARG;
+  return launch_kv_gather(cache, k_dst, v_dst, cu_tokens, start_pos, block_tables, max_blocks_per_seq, n_seqs,
+                          n_tokens, hip_stream);
+}
+
 size_t cronus_attn_mixed_workspace_bytes(const cronus_kv_cache* cache, const int32_t* prefix_lens,
                                          const int32_t* chunk_lens, int32_t n_seqs) {
   if (check_shape(cache) || n_seqs < 0 || (n_seqs > 0 && (!prefix_lens || !chunk_lens))) return 0;

@@ -92,5 +92,8 @@ int launch_attn(const AttnLaunch& a);
 int launch_kv_append(const cronus_kv_cache* cache, const void* k_src, const void* v_src,
                      const int32_t* cu_tokens, const int32_t* start_pos, const int32_t* block_tables,
                      int32_t max_blocks_per_seq, int32_t n_seqs, int32_t n_tokens, void* stream);
+int launch_kv_gather(const cronus_kv_cache* cache, void* k_dst, void* v_dst, const int32_t* cu_tokens,
+                     const int32_t* start_pos, const int32_t* block_tables, int32_t max_blocks_per_seq,
+                     int32_t n_seqs, int32_t n_tokens, void* stream);
 
 }  // namespace cronus
