@@ -197,6 +197,29 @@ __device__ __forceinline__ void store_row_bf16(unsigned short* row_ptr, const f3
     }
 }
 
+// Leave one lane's share of an unfinished row in a partial-result slot (O[32][D] fp32,
+// then m[32] in log2 units, then l[32]): `row` is the row's index inside the slot, lt the
+// row sum over both lanes of the row.
+template <int NDB, int D>
+__device__ __forceinline__ void store_partial_row(float* slot, int row, const f32x16 (&o)[NDB], float m_log2,
+                                                  float lt, int half) {
+  float* orow = slot + row * D;
+#pragma unroll
+  for (int db = 0; db < NDB; ++db)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      f32x4 lo4 = {o[db][8 * j], o[db][8 * j + 1], o[db][8 * j + 2], o[db][8 * j + 3]};
+      f32x4 hi4 = {o[db][8 * j + 4], o[db][8 * j + 5], o[db][8 * j + 6], o[db][8 * j + 7]};
+      float* dp = orow + 32 * db + 16 * j + 8 * half;
+      *reinterpret_cast<f32x4*>(dp) = lo4;
+      *reinterpret_cast<f32x4*>(dp + 4) = hi4;
+    }
+  if (half == 0) {
+    slot[kNarrowRows * D + row] = m_log2;
+    slot[kNarrowRows * D + kNarrowRows + row] = lt;
+  }
+}
+
 // ---------------------------------------- wide (chunk) tile, staged through registers
 // Used for the fp8 cache: codes are converted to bf16 once, on their way into LDS.
 template <int D, bool FP8, int QT>
@@ -350,13 +373,19 @@ __device__ __forceinline__ void run_wide_staged(const AttnParams& p, const WorkI
     buf ^= 1;
   }
 
-  // epilogue: normalise and store (wide items are never split)
+  // epilogue: normalise and store, or leave this span's partial result for the merge
+  static_assert(QT == 1, "one partial slot per wavefront");
   const float vmul = FP8 ? p.v_scale[it.kv_head] : 1.0f;
 #pragma unroll
   for (int qt = 0; qt < QT; ++qt) {
     const int r = row_base + qt * 32 + c32;
     const float lt = pair_sum(l[qt]);
     if (r < rows_valid) {
+      if (it.partial >= 0) {
+        float* ps = p.partials + (long long)(it.partial + wave) * (kNarrowRows * (D + 2));
+        store_partial_row<NDB, D>(ps, c32, o[qt], m[qt] * c, lt, half);
+        continue;
+      }
       const int t = r / gi_n, gi = r - t * gi_n;
       unsigned short* op = p.out + ((long long)(si.q_off + it.q_tok0 + t) * p.n_q_heads + it.head0 + gi) * D;
       store_row_bf16<NDB>(op, o[qt], vmul / lt, half);
@@ -481,8 +510,9 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
   const int rows_valid = it.n_tok * gi_n;
   const int row_base = wave * 32;
   const bool wave_has_rows = row_base < rows_valid;
-  const int kv_len = si.prefix_len + si.chunk_len;
-  const int pos0 = si.prefix_len + it.q_tok0;
+  // key positions are counted from the item's first key (a multiple of the tile size)
+  const int kv_len = si.prefix_len + si.chunk_len - it.kv_begin;
+  const int pos0 = si.prefix_len + it.q_tok0 - it.kv_begin;
   const float c = p.scale_log2e;
   const int wave_min_limit = pos0 + min(row_base, rows_valid - 1) / gi_n;
   const int wave_max_limit = wave_has_rows ? pos0 + min(row_base + 31, rows_valid - 1) / gi_n : -1;
@@ -508,10 +538,11 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
 #pragma unroll
     for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
 
-  const int* bt = p.block_tables + (long long)it.seq * p.max_blocks;
+  const int blk0 = it.kv_begin >> 4;
+  const int* bt = p.block_tables + (long long)it.seq * p.max_blocks + blk0;
   const long long head_stride = (long long)BLK_LDS;
-  const int n_sub = (it.kv_end - it.kv_begin + 31) >> 5;  // kv_begin = 0 for wide items
-  const int last_blk = si.n_blocks - 1;
+  const int n_sub = (it.kv_end - it.kv_begin + 31) >> 5;
+  const int last_blk = si.n_blocks - 1 - blk0;
   const int pr = perm32(c32);
 
   // ---- DMA of tile j: this wave moves UPW units of K and of V, all inside one block
@@ -689,8 +720,13 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
 
   const float lt = pair_sum(l);
   if (row_base + c32 < rows_valid) {
-    unsigned short* op = p.out + ((long long)(si.q_off + it.q_tok0 + t_row) * p.n_q_heads + it.head0 + gi_row) * D;
-    store_row_bf16<NDB>(op, o, 1.0f / lt, half);
+    if (it.partial >= 0) {
+      float* ps = p.partials + (long long)(it.partial + wave) * (kNarrowRows * (D + 2));
+      store_partial_row<NDB, D>(ps, c32, o, m * c, lt, half);
+    } else {
+      unsigned short* op = p.out + ((long long)(si.q_off + it.q_tok0 + t_row) * p.n_q_heads + it.head0 + gi_row) * D;
+      store_row_bf16<NDB>(op, o, 1.0f / lt, half);
+    }
   }
 }
 
@@ -920,21 +956,7 @@ __device__ __forceinline__ void run_narrow(const AttnParams& p, const WorkItem& 
         store_row_bf16<NDB>(op, o, vmul / lt, half);
       } else {
         float* ps = p.partials + (long long)it.partial * (kNarrowRows * (D + 2));
-        float* orow = ps + c32 * D;
-#pragma unroll
-        for (int db = 0; db < NDB; ++db)
-#pragma unroll
-          for (int j = 0; j < 2; ++j) {
-            f32x4 lo4 = {o[db][8 * j], o[db][8 * j + 1], o[db][8 * j + 2], o[db][8 * j + 3]};
-            f32x4 hi4 = {o[db][8 * j + 4], o[db][8 * j + 5], o[db][8 * j + 6], o[db][8 * j + 7]};
-            float* dp = orow + 32 * db + 16 * j + 8 * half;
-            *reinterpret_cast<f32x4*>(dp) = lo4;
-            *reinterpret_cast<f32x4*>(dp + 4) = hi4;
-          }
-        if (half == 0) {
-          ps[kNarrowRows * D + c32] = m * c;  // running maximum in log2 units
-          ps[kNarrowRows * D + kNarrowRows + c32] = lt;
-        }
+        store_partial_row<NDB, D>(ps, c32, o, m * c, lt, half);  // running maximum in log2 units
       }
     }
   }
@@ -960,21 +982,22 @@ __global__ __launch_bounds__(D) void attn_merge_kernel(AttnParams p) {
   const MergeItem mi = p.merges[blockIdx.x];
   const SeqInfo si = p.seqs[mi.seq];
   const int d = threadIdx.x;
-  const int rows = mi.n_tok * mi.n_heads;
   const size_t slot = (size_t)kNarrowRows * (D + 2);
+  const size_t step = slot * (size_t)mi.stride;
   const float vmul = FP8 ? p.v_scale[mi.kv_head] : 1.0f;
-  for (int r = 0; r < rows; ++r) {
+  for (int r = 0; r < mi.n_rows; ++r) {
     const float* base = p.partials + (size_t)mi.first_partial * slot;
     float mt = kNeg * 4.f;
-    for (int s = 0; s < mi.n_split; ++s) mt = fmaxf(mt, base[s * slot + kNarrowRows * D + r]);
+    for (int s = 0; s < mi.n_split; ++s) mt = fmaxf(mt, base[s * step + kNarrowRows * D + r]);
     float acc = 0.f, ls = 0.f;
     for (int s = 0; s < mi.n_split; ++s) {
-      const float* ps = base + s * slot;
+      const float* ps = base + s * step;
       const float w = __builtin_amdgcn_exp2f(ps[kNarrowRows * D + r] - mt);
       acc += ps[r * D + d] * w;
       ls += ps[kNarrowRows * D + kNarrowRows + r] * w;
     }
-    const int t = r / mi.n_heads, gi = r - t * mi.n_heads;
+    const int tr = mi.row0 + r;
+    const int t = tr / mi.n_heads, gi = tr - t * mi.n_heads;
     unsigned short* op = p.out + ((long long)(si.q_off + mi.q_tok0 + t) * p.n_q_heads + mi.head0 + gi) * D;
     const __bf16 v = (__bf16)(acc * vmul / ls);
     op[d] = __builtin_bit_cast(unsigned short, v);

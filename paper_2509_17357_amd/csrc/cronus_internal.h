@@ -34,12 +34,16 @@ struct WorkItem {
   int32_t n_tok;     // tokens in the tile; rows = n_tok * n_heads
   int32_t kv_begin;  // keys [kv_begin, kv_end) are processed by this item
   int32_t kv_end;
-  int32_t partial;   // < 0: writes final output; else index of its partial-result slot
+  int32_t partial;   // < 0: writes final output; else index of its (wide: first of kWaves) partial-result slot(s)
   int32_t wide;      // 1: chunk tile staged through LDS; 0: narrow (<= 32 rows), waves split keys; -1: idle slot
   int32_t pad0, pad1;
 };
 
-// Rows whose partial results (split over key spans) are combined by the merge kernel.
+// Rows whose partial results (split over key spans) are combined by the merge kernel:
+// rows row0 .. row0 + n_rows - 1 of the tile (row r = token r / n_heads, head r % n_heads);
+// span s left them in partial slot first_partial + s * stride, at slot rows 0 .. n_rows - 1.
+// A narrow item fills one slot (stride 1, row0 0); a split wide tile fills kWaves slots
+// per span, one per wavefront (stride kWaves, row0 = 32 * wavefront).
 struct MergeItem {
   int32_t first_partial;
   int32_t n_split;
@@ -49,6 +53,10 @@ struct MergeItem {
   int32_t n_heads;
   int32_t q_tok0;
   int32_t n_tok;
+  int32_t row0;
+  int32_t n_rows;
+  int32_t stride;
+  int32_t pad0;
 };
 
 struct Plan {

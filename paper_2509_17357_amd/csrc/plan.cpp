@@ -52,8 +52,11 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
   const int wide_rows = wide_rows_for(D, cache->kv_dtype);
   const int wide_tok = std::max(1, wide_rows / group);  // tokens per wide tile
 
-  // keys read by narrow items, to size the spans
+  // keys read by narrow items, to size the spans, and the cost of the wide tiles in the
+  // planner's unit (one key of a full wide tile = wide_rows / 128, one key of a narrow
+  // item = 1/2), to size the spans that long wide tiles are cut into
   long long narrow_keys = 0;
+  double wide_cost_total = 0;
   for (int s = 0; s < n_seqs; ++s) {
     const long long P = prefix_lens[s], C = chunk_lens[s];
     if (P < 0 || C < 0) return CRONUS_ERR_INVALID_ARG;
@@ -63,7 +66,20 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
     else {
       const long long rem = C % wide_tok;
       if (rem && rem * group <= kNarrowRows) narrow_keys += (P + C) * Hkv * n_groups;
+      const long long full = C / wide_tok;  // full tiles end at P + wide_tok, P + 2 wide_tok, ...
+      double keys = (double)full * P + (double)wide_tok * full * (full + 1) / 2;
+      if (rem && rem * group > kNarrowRows) keys += (double)(P + C) * std::max(0.25, (double)(rem * group) / wide_rows);
+      wide_cost_total += keys * (wide_rows / 128.0) * Hkv * n_groups;
     }
+  }
+  // no wide item should hold a CU for longer than about half of a CU's fair share
+  int wide_piece_keys = 0;
+  if (wide_cost_total > 0) {
+    const double fair = (wide_cost_total + 0.5 * narrow_keys) / std::max(n_cus, 1);
+    const double keys = 0.5 * fair / (wide_rows / 128.0);
+    constexpr int kMinPiece = 8 * kWideKvTile;
+    wide_piece_keys = (int)std::min<double>(std::max<double>(keys, kMinPiece), 1 << 30);
+    wide_piece_keys = (wide_piece_keys + kWideKvTile - 1) / kWideKvTile * kWideKvTile;
   }
   const long long target_items = (long long)std::max(n_cus, 1) * 8;
   long long span = (narrow_keys + target_items - 1) / target_items;
@@ -87,7 +103,7 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
     const int per = (int)(((kv_total + n_split - 1) / n_split + kNarrowKvStep - 1) / kNarrowKvStep * kNarrowKvStep);
     n_split = (kv_total + per - 1) / per;
     if (n_split > 1) {
-      sc.merges.push_back(MergeItem{(int32_t)n_partials, n_split, s, kvh, head0, nh, q_tok0, n_tok});
+      sc.merges.push_back(MergeItem{(int32_t)n_partials, n_split, s, kvh, head0, nh, q_tok0, n_tok, 0, n_tok * nh, 1, 0});
       n_merge_rows += (int64_t)n_tok * nh;
     }
     for (int i = 0; i < n_split; ++i) {
@@ -121,17 +137,40 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
             add_narrow(s, kvh, head0, nh, t0, nt, P + t0 + nt);
             continue;
           }
-          WorkItem w{};
-          w.seq = s; w.kv_head = kvh; w.head0 = head0; w.n_heads = nh; w.q_tok0 = t0; w.n_tok = nt;
-          w.kv_begin = 0;
-          w.kv_end = P + t0 + nt;
-          w.partial = -1;
-          w.wide = 1;
+          // A tile whose keys alone would keep one CU busy for longer than about half of
+          // a CU's fair share of the whole launch is cut into spans of whole K/V tiles;
+          // each span leaves partial results (one slot per wavefront) for the merge.
+          const int kv_total = P + t0 + nt;
           const float rows_frac = std::max(0.25f, (float)(nt * nh) / wide_rows);
-          const float cost = (float)w.kv_end * (wide_rows / 128.0f) * rows_frac;
-          sc.wide.push_back(w);
-          sc.wide_cost.push_back(cost);
-          g.cost += cost;
+          const float cost_per_key = (wide_rows / 128.0f) * rows_frac;
+          int n_split = 1;
+          if (wide_piece_keys > 0 && kv_total > wide_piece_keys + wide_piece_keys / 2)
+            n_split = (kv_total + wide_piece_keys - 1) / wide_piece_keys;
+          const int per = ((kv_total + n_split - 1) / n_split + kWideKvTile - 1) / kWideKvTile * kWideKvTile;
+          n_split = (kv_total + per - 1) / per;
+          const int rows = nt * nh;
+          if (n_split > 1) {
+            for (int wv = 0; wv * kNarrowRows < rows; ++wv)
+              sc.merges.push_back(MergeItem{(int32_t)n_partials + wv, n_split, s, kvh, head0, nh, t0, nt,
+                                            wv * kNarrowRows, std::min(kNarrowRows, rows - wv * kNarrowRows), kWaves, 0});
+            n_merge_rows += rows;
+          }
+          for (int i = 0; i < n_split; ++i) {
+            WorkItem w{};
+            w.seq = s; w.kv_head = kvh; w.head0 = head0; w.n_heads = nh; w.q_tok0 = t0; w.n_tok = nt;
+            w.kv_begin = i * per;
+            w.kv_end = std::min(kv_total, (i + 1) * per);
+            w.partial = -1;
+            if (n_split > 1) {
+              w.partial = (int32_t)n_partials;
+              n_partials += kWaves;
+            }
+            w.wide = 1;
+            const float cost = (float)(w.kv_end - w.kv_begin) * cost_per_key;
+            sc.wide.push_back(w);
+            sc.wide_cost.push_back(cost);
+            g.cost += cost;
+          }
         }
         g.end = (int32_t)sc.wide.size();
         if (g.end > g.begin) sc.groups.push_back(g);

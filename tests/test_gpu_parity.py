@@ -69,6 +69,30 @@ def test_long_decode_is_split_and_merged():
     U.assert_within_tolerance(run_batch(batch))
 
 
+SPLIT_WIDE = [
+    # (shape, prefix_lens, chunk_lens): few wide tiles with many keys -> key spans + merge
+    (W.SHAPE_8B, [3000, 40], [100, 1]),                       # last span holds the causal edge
+    (W.SHAPE_8B, [1000], [130]),                              # two wide tiles and a narrow tail of two tokens
+    (W.HeadShape(8, 2, 64), [2500, 777], [70, 1]),            # D = 64
+    (W.HeadShape(28, 4, 128), [1900], [80]),                  # G = 7: wavefronts start inside a token
+    (W.HeadShape(16, 2, 128, "fp8"), [2100, 300], [64, 1]),   # fp8 cache (register-staged wide path)
+    (W.SHAPE_8B, [6000, 1999, 1999], [512 - 2, 1, 1]),        # a paper-shaped iteration: 512 batched tokens
+]
+
+
+@pytest.mark.parametrize("case", range(len(SPLIT_WIDE)))
+def test_split_wide_tiles(case):
+    shape, P, C = SPLIT_WIDE[case]
+    batch = W.custom_batch(shape, P, C, seed=4350 + case)
+    it = DeviceIteration(batch)
+    items = B.cronus_attn_mixed_plan_items(it.cache, batch.prefix_lens, batch.chunk_lens)
+    f = {n: i for i, n in enumerate(B.PLAN_ITEM_FIELDS)}
+    wide = items[items[:, f["wide"]] == 1]
+    assert (wide[:, f["partial"]] >= 0).any() and (wide[:, f["kv_begin"]] > 0).any()
+    del it
+    U.assert_within_tolerance(run_batch(batch))
+
+
 def test_config2_scaled_down():
     U.assert_within_tolerance(run_batch(W.draw_batch(2, scale=0.25)))
 

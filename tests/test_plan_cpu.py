@@ -36,7 +36,7 @@ def check_plan(shape, P, C):
         assert 0 <= t0 and nt >= 1 and t0 + nt <= C[s]
         assert nt * nh <= (256 if wide else 32)
         if wide:
-            assert kb == 0 and ke == P[s] + t0 + nt and part == -1
+            assert kb % 64 == 0 and kb < ke <= P[s] + t0 + nt   # whole K/V tiles of 64 keys
         else:
             assert kb % 256 == 0 and kb < ke <= P[s] + t0 + nt
         for h in range(h0, h0 + nh):
@@ -56,8 +56,11 @@ def check_plan(shape, P, C):
                 else:
                     assert spans[0][2] == -1
     assert not cover
-    parts = real[real[:, F["partial"]] >= 0][:, F["partial"]]
-    assert sorted(parts.tolist()) == list(range(stats["partials"]))          # each slot written once
+    # each partial slot belongs to one item: a narrow item owns one, a split wide tile one per wavefront
+    slots = []
+    for it in real[real[:, F["partial"]] >= 0]:
+        slots += list(range(int(it[F["partial"]]), int(it[F["partial"]]) + (8 if it[F["wide"]] == 1 else 1)))
+    assert sorted(slots) == list(range(stats["partials"]))
     return items, stats
 
 
@@ -103,7 +106,24 @@ def test_plan_queues_follow_xcd_order():
     load = np.zeros(8)
     for i, it in enumerate(items):
         if it[F["wide"]] == 1:
-            load[i % 8] += 2.0 * it[F["kv_end"]]
+            load[i % 8] += 2.0 * (it[F["kv_end"]] - it[F["kv_begin"]])
         elif it[F["wide"]] == 0:
             load[i % 8] += 0.5 * (it[F["kv_end"]] - it[F["kv_begin"]])
     assert load.max() <= 1.1 * load.mean()
+
+
+def test_few_long_wide_tiles_are_split_over_keys():
+    """A paper-shaped iteration (one chunk of at most 512 tokens against a long prefix) has
+    only 64 wide tiles for 256 CUs: each is cut into key spans so that every CU gets work,
+    while a batch with many tiles per CU is left alone."""
+    sh = W.SHAPE_8B
+    items, stats = check_plan(sh, [32768] + [999] * 16, [496] + [1] * 16)
+    wide = items[items[:, F["wide"]] == 1]
+    tiles = {(int(i[F["kv_head"]]), int(i[F["q_tok0"]])) for i in wide}
+    assert len(tiles) == 8 * 8 and len(wide) >= 4 * len(tiles)
+    span = wide[:, F["kv_end"]] - wide[:, F["kv_begin"]]
+    assert span.max() <= 2 * span[span > 256].min() + 64   # spans of one size, up to the tail
+    b = W.draw_batch(3)
+    items3, _ = plan_for(b.shape, b.prefix_lens, b.chunk_lens)
+    w3 = items3[items3[:, F["wide"]] == 1]
+    assert (w3[:, F["kv_begin"]] == 0).all() and (w3[:, F["partial"]] == -1).all()
