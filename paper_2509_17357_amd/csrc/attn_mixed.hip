@@ -977,30 +977,37 @@ __global__ __launch_bounds__(kThreads) void attn_mixed_kernel(AttnParams p) {
 
 // Combine the partial results of a row group that was split over key spans:
 // out = sum_s O_s 2^(m_s - M) / sum_s l_s 2^(m_s - M), M = max_s m_s (m in log2 units).
+// D/4 threads share a row (four dims each), so a work-group of 256 threads combines
+// 1024/D rows at a time; the loads of the spans are independent of each other.
+constexpr int kMergeThreads = 256;
 template <int D, bool FP8>
-__global__ __launch_bounds__(D) void attn_merge_kernel(AttnParams p) {
+__global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(AttnParams p) {
+  constexpr int TPR = D / 4, RPP = kMergeThreads / TPR;
   const MergeItem mi = p.merges[blockIdx.x];
   const SeqInfo si = p.seqs[mi.seq];
-  const int d = threadIdx.x;
+  const int dq = threadIdx.x % TPR;
   const size_t slot = (size_t)kNarrowRows * (D + 2);
   const size_t step = slot * (size_t)mi.stride;
   const float vmul = FP8 ? p.v_scale[mi.kv_head] : 1.0f;
-  for (int r = 0; r < mi.n_rows; ++r) {
-    const float* base = p.partials + (size_t)mi.first_partial * slot;
+  const float* base = p.partials + (size_t)mi.first_partial * slot;
+  for (int r = threadIdx.x / TPR; r < mi.n_rows; r += RPP) {
     float mt = kNeg * 4.f;
     for (int s = 0; s < mi.n_split; ++s) mt = fmaxf(mt, base[s * step + kNarrowRows * D + r]);
-    float acc = 0.f, ls = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    float ls = 0.f;
     for (int s = 0; s < mi.n_split; ++s) {
       const float* ps = base + s * step;
       const float w = __builtin_amdgcn_exp2f(ps[kNarrowRows * D + r] - mt);
-      acc += ps[r * D + d] * w;
+      const f32x4 o4 = *reinterpret_cast<const f32x4*>(ps + r * D + 4 * dq);
+      acc += o4 * w;
       ls += ps[kNarrowRows * D + kNarrowRows + r] * w;
     }
     const int tr = mi.row0 + r;
     const int t = tr / mi.n_heads, gi = tr - t * mi.n_heads;
-    unsigned short* op = p.out + ((long long)(si.q_off + mi.q_tok0 + t) * p.n_q_heads + mi.head0 + gi) * D;
-    const __bf16 v = (__bf16)(acc * vmul / ls);
-    op[d] = __builtin_bit_cast(unsigned short, v);
+    unsigned short* op = p.out + ((long long)(si.q_off + mi.q_tok0 + t) * p.n_q_heads + mi.head0 + gi) * D + 4 * dq;
+    const float f = vmul / ls;
+    u32x2 w2 = {pack_bf16(acc[0] * f, acc[1] * f), pack_bf16(acc[2] * f, acc[3] * f)};
+    *reinterpret_cast<u32x2*>(op) = w2;
   }
 }
 
@@ -1028,7 +1035,7 @@ int launch_typed(const AttnLaunch& a, const AttnParams& p) {
     if (timed && hipEventRecord(static_cast<hipEvent_t>(a.ev_stop), s) != hipSuccess) return CRONUS_ERR_HIP;
   }
   if (pl.n_merge > 0) {
-    hipLaunchKernelGGL((attn_merge_kernel<D, FP8>), dim3((unsigned)pl.n_merge), dim3(D), 0, s, p);
+    hipLaunchKernelGGL((attn_merge_kernel<D, FP8>), dim3((unsigned)pl.n_merge), dim3(kMergeThreads), 0, s, p);
     if (hipGetLastError() != hipSuccess) return CRONUS_ERR_HIP;
   }
   return CRONUS_OK;

@@ -72,12 +72,14 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
       wide_cost_total += keys * (wide_rows / 128.0) * Hkv * n_groups;
     }
   }
-  // no wide item should hold a CU for longer than about half of a CU's fair share
+  // no wide item should hold a CU for much longer than three quarters of a CU's fair share
+  // (measured on paper-shaped iterations: smaller spans pay more for their prologue and the
+  // merge than they gain in balance), and no span is shorter than 16 K/V tiles
   int wide_piece_keys = 0;
   if (wide_cost_total > 0) {
     const double fair = (wide_cost_total + 0.5 * narrow_keys) / std::max(n_cus, 1);
-    const double keys = 0.5 * fair / (wide_rows / 128.0);
-    constexpr int kMinPiece = 8 * kWideKvTile;
+    const double keys = 0.75 * fair / (wide_rows / 128.0);
+    constexpr int kMinPiece = 16 * kWideKvTile;
     wide_piece_keys = (int)std::min<double>(std::max<double>(keys, kMinPiece), 1 << 30);
     wide_piece_keys = (wide_piece_keys + kWideKvTile - 1) / kWideKvTile * kWideKvTile;
   }
@@ -137,8 +139,8 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
             add_narrow(s, kvh, head0, nh, t0, nt, P + t0 + nt);
             continue;
           }
-          // A tile whose keys alone would keep one CU busy for longer than about half of
-          // a CU's fair share of the whole launch is cut into spans of whole K/V tiles;
+          // A tile whose keys alone would keep one CU busy for much longer than a CU's fair
+          // share of the whole launch is cut into spans of whole K/V tiles;
           // each span leaves partial results (one slot per wavefront) for the merge.
           const int kv_total = P + t0 + nt;
           const float rows_frac = std::max(0.25f, (float)(nt * nh) / wide_rows);
