@@ -8,6 +8,7 @@ import pytest
 import torch
 
 from oracle import cronus_oracle as orc
+from paper_2509_17357_amd import binding as B
 from paper_2509_17357_amd import workloads as W
 from paper_2509_17357_amd.runtime import DeviceIteration, bf16_tensor_from_bits, bits_from_bf16_tensor
 
@@ -24,6 +25,28 @@ def test_full_batch_every_row(cid):
     it.setup_decode_context()
     it.step()
     torch.cuda.synchronize()
+    ref = U.oracle_attention(batch, bits_from_bf16_tensor(it.q), U.oracle_kv_values(batch, kv_bits), it.sm_scale)
+    rep = U.error_report(batch, bits_from_bf16_tensor(it.out), ref)
+    print(batch.name, rep)
+    U.assert_within_tolerance(rep)
+
+
+def test_paper_shaped_iteration_long_context_every_row():
+    """One iteration as the paper runs them (section 5.1: 512 batched tokens): a chunk of
+    496 tokens whose request already has 16384 tokens of context, next to 16 decodes.
+    Its 64 wide tiles are cut into key spans and merged (the planner's answer to a launch
+    with fewer tiles than CUs); every output row is checked."""
+    rng = np.random.default_rng(515)
+    P = [16384] + rng.integers(1500, 6000, 16).tolist()
+    C = [496] + [1] * 16
+    batch = W.custom_batch(W.SHAPE_8B, P, C, seed=5150)
+    it = DeviceIteration(batch, pool_fill=0x7FC1)
+    kv_bits = it.load_host_inputs()
+    it.setup_decode_context()
+    it.step()
+    torch.cuda.synchronize()
+    stats = B.cronus_attn_mixed_plan_stats(it.cache, batch.prefix_lens, batch.chunk_lens)
+    assert stats["wide_items"] >= 3 * 64
     ref = U.oracle_attention(batch, bits_from_bf16_tensor(it.q), U.oracle_kv_values(batch, kv_bits), it.sm_scale)
     rep = U.error_report(batch, bits_from_bf16_tensor(it.out), ref)
     print(batch.name, rep)
