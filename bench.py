@@ -11,8 +11,10 @@ resident in HBM before the timed region.  Prints ONE JSON line.
                   [--no-cpu-baseline]
 
 The headline workload is the Llama-3-8B-shaped batch (benchmark configs[1]); the
-prefill-heavy and decode-heavy batches, which carry the MFMA and HBM roofline targets,
-are timed as well and reported under "other_workloads".
+prefill-heavy and decode-heavy batches, which carry the MFMA and HBM roofline targets, and
+the 70B-shaped batch with the fp8 cache are timed as well and reported under
+"other_workloads"; "scatter_gather" has cronus_kv_append / cronus_kv_gather as pure
+data movement.
 """
 from __future__ import annotations
 
@@ -109,6 +111,44 @@ def time_workload(name, steps, warmup, trial=0):
     return res, batch
 
 
+def time_scatter_gather(reps=5):
+    """cronus_kv_append and cronus_kv_gather as pure data movement: the decode contexts of
+    the decode-heavy batch (about 1.2 M tokens, 4.8 GB of K+V) scattered into the paged pool
+    and exported again.  GB/s counts what the call must move: source read + destination write."""
+    import torch
+    from paper_2509_17357_amd import binding as B
+    from paper_2509_17357_amd import workloads as W
+    from paper_2509_17357_amd.runtime import DeviceIteration
+
+    batch = W.draw_batch(WORKLOADS["decode_heavy"])
+    it = DeviceIteration(batch, device="cuda:0")
+    it.load_device_inputs()
+    sh = batch.shape
+    n = it.n_ctx_tokens
+    kd, vd = torch.empty_like(it.ctx_k), torch.empty_like(it.ctx_v)
+    stream = torch.cuda.current_stream().cuda_stream
+    gather = lambda: B.cronus_kv_gather(it.cache, kd, vd, it.cu_ctx, it.zero_pos, it.block_tables, batch.max_blocks,
+                                        batch.n_seqs, n, stream)
+    out = {}
+    for name, fn in (("kv_append", it.setup_decode_context), ("kv_gather", gather)):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        nbytes = 2 * n * sh.n_kv_heads * sh.head_dim * 2 * 2  # K and V, read + write, bf16
+        out[name] = {"tokens": n, "ms": ms, "algorithmic_bytes": nbytes, "gbs": nbytes / (ms * 1e-3) / 1e9,
+                     "pct_hbm_peak": 100.0 * nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+    assert torch.equal(kd, it.ctx_k) and torch.equal(vd, it.ctx_v), "gather(append(x)) != x"
+    del it, kd, vd
+    torch.cuda.empty_cache()
+    return out
+
+
 def cpu_baseline(batch, budget_s=12.0, min_s=10.0):
     """The fp64 oracle, untuned, on a bounded stratified sample of the same batch:
     chunk sequences and decode sequences are sampled separately (whole sequences, in
@@ -197,10 +237,14 @@ def main():
 
     main_res, batch = time_workload(args.workload, args.steps, args.warmup)
     others = {}
+    scatter_gather = None
     if not args.no_extra:
         for name in ("prefill_heavy", "decode_heavy"):
             if name != args.workload:
                 others[name], _ = time_workload(name, max(5, args.steps // 2), max(2, args.warmup // 2))
+        if args.workload != "llama_70b_fp8":
+            others["llama_70b_fp8"], _ = time_workload("llama_70b_fp8", 5, 2)
+        scatter_gather = time_scatter_gather()
     sh = batch.shape
     line = {
         "metric": "mixed-batch attention tokens/s; TFLOP/s and HBM GB/s as % of MI355X peak",
@@ -222,6 +266,7 @@ def main():
         "detail": main_res,
         "roofline": main_res["roofline"],
         "other_workloads": others,
+        "scatter_gather": scatter_gather,
     }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(batch)
