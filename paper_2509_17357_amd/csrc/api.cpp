@@ -148,9 +148,14 @@ int64_t cronus_attn_mixed_plan_items(const cronus_kv_cache* cache, const int32_t
   if (int rc = build_plan(cache, prefix_lens, chunk_lens, n_seqs, 0x7fffffff / kBlock, device_cus(), &plan)) return -rc;
   std::vector<unsigned char> buf(plan.upload_bytes);
   write_plan(&plan, buf.data());
-  static_assert(sizeof(WorkItem) == 12 * sizeof(int32_t), "plan item layout");
   const int64_t n = std::min<int64_t>(capacity, plan.n_items);
-  if (n > 0) std::memcpy(items, buf.data() + plan.off_items, (size_t)n * sizeof(WorkItem));
+  const WorkItem* wi = reinterpret_cast<const WorkItem*>(buf.data() + plan.off_items);
+  for (int64_t i = 0; i < n; ++i) {
+    const WorkItem& w = wi[i];
+    const int32_t row[12] = {w.seq, w.kv_head, w.head0, w.n_heads, w.q_tok0, w.n_tok, w.kv_begin, w.kv_end,
+                             w.partial, w.wide, 0, 0};
+    std::memcpy(items + 12 * i, row, sizeof(row));
+  }
   return plan.n_items;
 }
 

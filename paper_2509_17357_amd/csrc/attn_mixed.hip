@@ -22,8 +22,8 @@
 
 #include "cronus_internal.h"
 
-#ifndef CRONUS_SPLIT_ISSUE
-#define CRONUS_SPLIT_ISSUE 1
+#ifndef CRONUS_SKEW
+#define CRONUS_SKEW 1
 #endif
 #ifndef CRONUS_HINT
 #define CRONUS_HINT 7  // VALU instructions issued per MFMA in the interleaved block
@@ -236,7 +236,7 @@ __device__ __forceinline__ void run_wide_staged(const AttnParams& p, const WorkI
   const int tid = threadIdx.x;
   const int lane = tid & 63, half = lane >> 5, c32 = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const SeqInfo si = p.seqs[it.seq];
+  const SeqInfo si = {it.prefix_len, it.chunk_len, it.q_off, it.n_blocks};
   const int gi_n = it.n_heads;
   const int rows_valid = it.n_tok * gi_n;
   const int row_base = wave * 32 * QT;
@@ -505,7 +505,7 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
   const int tid = threadIdx.x;
   const int lane = tid & 63, half = lane >> 5, c32 = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const SeqInfo si = p.seqs[it.seq];
+  const SeqInfo si = {it.prefix_len, it.chunk_len, it.q_off, it.n_blocks};
   const int gi_n = it.n_heads;
   const int rows_valid = it.n_tok * gi_n;
   const int row_base = wave * 32;
@@ -520,16 +520,14 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
   const int r = min(row_base + c32, rows_valid - 1);
   const int t_row = r / gi_n, gi_row = r - t_row * gi_n;
   const int limit = pos0 + t_row;
-  bf16x8 qreg[NSTEP];
+  // Q is requested first and waited for only after the first K/V tiles have been
+  // requested too: one memory latency, not two, before the first product
+  u32x4 qraw[NSTEP];
   {
     const unsigned short* qp =
         p.q + ((long long)(si.q_off + it.q_tok0 + t_row) * p.n_q_heads + it.head0 + gi_row) * D + 8 * half;
 #pragma unroll
-    for (int s = 0; s < NSTEP; ++s) {
-      u32x4 qv = *reinterpret_cast<const u32x4*>(qp + 16 * s);
-      asm volatile("" : "+v"(qv));  // wait for the load here, not inside the pipeline
-      qreg[s] = as_bf16x8(qv);
-    }
+    for (int s = 0; s < NSTEP; ++s) qraw[s] = *reinterpret_cast<const u32x4*>(qp + 16 * s);
   }
   f32x16 o[NDB];
   float m = kNeg, l = 0.f;
@@ -608,6 +606,7 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
   auto active = [&](int u) { return 32 * u <= wave_max_limit; };
 
   u32x4 pp[2];
+  bf16x8 qreg[NSTEP];
   auto qk = [&](f32x16& s) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) s[i] = 0.f;
@@ -619,6 +618,11 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
   // ---- prologue: first tiles in flight, tile 0 landed everywhere, S(0), K(1) on its way
 #pragma unroll
   for (int j = 0; j < kAhead; ++j) issue_tile(j);
+#pragma unroll
+  for (int s = 0; s < NSTEP; ++s) {
+    asm volatile("" : "+v"(qraw[s]));  // the wait for Q sits here, not inside the pipeline
+    qreg[s] = as_bf16x8(qraw[s]);
+  }
   wait_vmcnt<NI * (kAhead - 1)>();
   __builtin_amdgcn_s_barrier();
   f32x16 s_even, s_odd;  // S(u) of even / odd sub-tiles
@@ -664,7 +668,22 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
   // the S(u+1) products and the exponentials of S(u), which are independent, sit in one
   // block and are interleaved: the wave keeps issuing VALU work while each MFMA of the
   // dependent chain is in the pipe.
+  // The two waves of a SIMD (w and w + 4) take their once-per-tile hand-over at different
+  // points of the step: waves 0-3 between the S products and the O products, waves 4-7
+  // before the S products.  The barrier therefore releases them half a step apart, and
+  // while one wave of a SIMD is in its VALU-heavy half (exponentials interleaved with the
+  // S products) the other is in its MFMA-only half (O products), instead of both
+  // competing for the same unit.
+  const bool early_sync = CRONUS_SKEW && wave >= kWaves / 2;
+  auto tile_sync = [&](int jn) {
+    wait_vmcnt<NI>();
+    __builtin_amdgcn_s_barrier();
+    issue_part(jn, 0);
+    issue_part(jn, 1);
+  };
   auto fast_step = [&](int u, f32x16& s_cur, f32x16& s_nxt, bool opens_tile) {
+    const int jn = (u >> 1) + kAhead;
+    if (opens_tile && early_sync) tile_sync(jn);
     issue_v(u);              // lands during the block below
     lds_land<NSTEP>(ka);     // K(u+1), issued before the previous step's O products
     qk(s_nxt);
@@ -684,12 +703,8 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
       tile_sum = softmax_exp_part(s_cur, c, m, pp);
     }
     l += tile_sum;
-    const int jn = (u >> 1) + kAhead;
     if (opens_tile) {
-      wait_vmcnt<NI>();
-      __builtin_amdgcn_s_barrier();
-      issue_part(jn, 0);
-      issue_part(jn, 1);
+      if (!early_sync) tile_sync(jn);
     } else if constexpr (UPW > 1) {
       issue_part(jn, 2);
       issue_part(jn, 3);
@@ -756,7 +771,7 @@ __device__ __forceinline__ void run_narrow(const AttnParams& p, const WorkItem& 
   const int tid = threadIdx.x;
   const int lane = tid & 63, half = lane >> 5, c32 = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const SeqInfo si = p.seqs[it.seq];
+  const SeqInfo si = {it.prefix_len, it.chunk_len, it.q_off, it.n_blocks};
   const int gi_n = it.n_heads;
   const int rows_valid = it.n_tok * gi_n;  // <= 32
   const int kv_len = si.prefix_len + si.chunk_len;
@@ -767,19 +782,24 @@ __device__ __forceinline__ void run_narrow(const AttnParams& p, const WorkItem& 
   const int r = min(c32, rows_valid - 1);
   const int t_row = r / gi_n, gi_row = r - t_row * gi_n;
   const int limit = pos0 + t_row;
+  // Q is requested here and waited for after the first block-table entries and K/V
+  // chunks have been requested as well (pin_q below): the latencies overlap, and the wait
+  // is not left to the streaming loop, where it would be a wait for every load in flight
   bf16x8 qreg[NSTEP];
+  u32x4 qraw[NSTEP];
   {
     const unsigned short* qp =
         p.q + ((long long)(si.q_off + it.q_tok0 + t_row) * p.n_q_heads + it.head0 + gi_row) * D + 8 * half;
 #pragma unroll
-    for (int s = 0; s < NSTEP; ++s) {
-      u32x4 qv = *reinterpret_cast<const u32x4*>(qp + 16 * s);
-      // pin the wait for this load here: inside the streaming loop it would have to
-      // be a wait for every load in flight
-      asm volatile("" : "+v"(qv));
-      qreg[s] = as_bf16x8(qv);
-    }
+    for (int s = 0; s < NSTEP; ++s) qraw[s] = *reinterpret_cast<const u32x4*>(qp + 16 * s);
   }
+  auto pin_q = [&]() {
+#pragma unroll
+    for (int s = 0; s < NSTEP; ++s) {
+      asm volatile("" : "+v"(qraw[s]));
+      qreg[s] = as_bf16x8(qraw[s]);
+    }
+  };
 
   f32x16 o[NDB];
   float m = kNeg, l = 0.f;
@@ -862,6 +882,7 @@ __device__ __forceinline__ void run_narrow(const AttnParams& p, const WorkItem& 
       issue_k(0);
       issue_v(0);
     }
+    pin_q();
     for (int j = 0; j < n_iter; ++j) {
       const int u = wave + kWaves * j;
       const bool has_next = j + 1 < n_iter;
@@ -910,6 +931,7 @@ __device__ __forceinline__ void run_narrow(const AttnParams& p, const WorkItem& 
     };
     NarrowOps<D, FP8> a, b;
     load_ops(a, wave);
+    pin_q();
     for (int u = wave; u < n_sub; u += 2 * kWaves) {
       load_ops(b, u + kWaves);
       consume(a, u);

@@ -36,8 +36,12 @@ struct WorkItem {
   int32_t kv_end;
   int32_t partial;   // < 0: writes final output; else index of its (wide: first of kWaves) partial-result slot(s)
   int32_t wide;      // 1: chunk tile staged through LDS; 0: narrow (<= 32 rows), waves split keys; -1: idle slot
+  // copy of the sequence's record, so that a work-group needs one dependent load less
+  // before it can address Q and the block table
+  int32_t prefix_len, chunk_len, q_off, n_blocks;
   int32_t pad0, pad1;
 };
+static_assert(sizeof(WorkItem) == 64, "one work item = one 64-byte line");
 
 // Rows whose partial results (split over key spans) are combined by the merge kernel:
 // rows row0 .. row0 + n_rows - 1 of the tile (row r = token r / n_heads, head r % n_heads);

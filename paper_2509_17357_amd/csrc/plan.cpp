@@ -277,7 +277,13 @@ void write_plan(const Plan* plan, void* host_buf) {
     const size_t k = i / kXcds, x = i % kXcds;
     if (k < sc.queue[x].size()) {
       const int32_t ref = sc.queue[x][k];
-      wi[i] = ref >= 0 ? sc.wide[(size_t)ref] : sc.narrow[(size_t)~ref];
+      WorkItem w = ref >= 0 ? sc.wide[(size_t)ref] : sc.narrow[(size_t)~ref];
+      const SeqInfo& si = sc.seqs[(size_t)w.seq];
+      w.prefix_len = si.prefix_len;
+      w.chunk_len = si.chunk_len;
+      w.q_off = si.q_off;
+      w.n_blocks = si.n_blocks;
+      wi[i] = w;
     } else {
       wi[i] = idle;
     }
