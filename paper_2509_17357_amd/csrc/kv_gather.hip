@@ -9,6 +9,7 @@
 #include <hip/hip_runtime.h>
 
 #include "cronus_internal.h"
+#include "paged_rows.h"
 
 namespace cronus {
 namespace {
@@ -33,12 +34,7 @@ __global__ __launch_bounds__(256) void kv_gather_kernel(
   const int slot = t & 15, dc = t >> 4;
   const int n_dc = head_dim >> 3;
 
-  int lo = 0, hi = n_seqs;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if ((cu_tokens[mid] >> 4) + 2 * mid <= g) lo = mid; else hi = mid;
-  }
-  const int s = lo;
+  const int s = find_sequence(cu_tokens, n_seqs, g);
   const int row0 = cu_tokens[s], n_rows = cu_tokens[s + 1] - row0;
   const int start = start_pos[s];
   const int j = g - ((row0 >> 4) + 2 * s);
