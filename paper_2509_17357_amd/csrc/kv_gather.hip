@@ -34,9 +34,8 @@ __global__ __launch_bounds__(256) void kv_gather_kernel(
   const int slot = t & 15, dc = t >> 4;
   const int n_dc = head_dim >> 3;
 
-  const int s = find_sequence(cu_tokens, n_seqs, g);
-  const int row0 = cu_tokens[s], n_rows = cu_tokens[s + 1] - row0;
-  const int start = start_pos[s];
+  const SeqRows sr = find_sequence(cu_tokens, start_pos, n_seqs, g);
+  const int s = sr.seq, row0 = sr.row0, n_rows = sr.n_rows, start = sr.start;
   const int j = g - ((row0 >> 4) + 2 * s);
   const int bi = (start >> 4) + j;
   const int pos_lo = max(start, bi * 16), pos_hi = min(start + n_rows, bi * 16 + 16);
