@@ -93,6 +93,33 @@ def test_split_wide_tiles(case):
     U.assert_within_tolerance(run_batch(batch))
 
 
+def test_full_prompt_prefill_without_prefix():
+    """prefix_len = 0: the whole prompt is one chunk (what the partial prefill instance runs
+    on its side of the hand-over, section 4.2), here 1500 tokens = 23 full tiles and a
+    28-token remainder, next to a second, short prompt."""
+    batch = W.custom_batch(W.SHAPE_8B, [0, 0], [1500, 77], seed=4360)
+    U.assert_within_tolerance(run_batch(batch))
+
+
+def test_many_short_decodes_and_empty_sequences():
+    """600 decodes with contexts of 1 .. 300 keys, every fifth sequence empty (chunk_len 0)."""
+    rng = np.random.default_rng(4370)
+    P = rng.integers(0, 300, 600)
+    C = np.where(np.arange(600) % 5 == 4, 0, 1)
+    batch = W.custom_batch(W.HeadShape(16, 4, 64), P.tolist(), C.tolist(), seed=4370)
+    U.assert_within_tolerance(run_batch(batch))
+
+
+def test_very_long_decode_context():
+    """One decode over 131072 keys (32 spans merged) next to a short one."""
+    batch = W.custom_batch(W.HeadShape(8, 2, 128), [131071, 40], [1, 1], seed=4380)
+    it = DeviceIteration(batch)
+    stats = B.cronus_attn_mixed_plan_stats(it.cache, batch.prefix_lens, batch.chunk_lens)
+    assert stats["partials"] >= 2 * 32
+    del it
+    U.assert_within_tolerance(run_batch(batch))
+
+
 def test_config2_scaled_down():
     U.assert_within_tolerance(run_batch(W.draw_batch(2, scale=0.25)))
 
