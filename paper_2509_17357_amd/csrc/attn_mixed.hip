@@ -22,9 +22,6 @@
 
 #include "cronus_internal.h"
 
-#ifndef CRONUS_SKEW
-#define CRONUS_SKEW 1
-#endif
 #ifndef CRONUS_HINT
 #define CRONUS_HINT 7  // VALU instructions issued per MFMA in the interleaved block
 #endif
@@ -403,21 +400,10 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"i"(N) : "memory");
 }
 
-#ifndef CRONUS_DMA_DWORD
-#define CRONUS_DMA_DWORD 0
-#endif
-// Copy 1 KiB, global -> LDS, by one wave: g and dst are the wave's bases (no lane term).
-constexpr int kDmaPerKiB = CRONUS_DMA_DWORD ? 4 : 1;
+// Copy 1 KiB, global -> LDS, by one wave (lane i moves bytes [16 i, 16 i + 16)): g and dst
+// are the wave's bases (no lane term).  Four 4-byte-per-lane instructions measured the same.
 __device__ __forceinline__ void dma_1k(const unsigned char* g, lds_byte* dst, int lane) {
-#if CRONUS_DMA_DWORD
-  const unsigned char* gl = g + lane * 4;
-  __builtin_amdgcn_global_load_lds(gl, dst, 4, 0, 0);
-  __builtin_amdgcn_global_load_lds(gl, dst, 4, 256, 0);
-  __builtin_amdgcn_global_load_lds(gl, dst, 4, 512, 0);
-  __builtin_amdgcn_global_load_lds(gl, dst, 4, 768, 0);
-#else
   __builtin_amdgcn_global_load_lds(g + lane * 16, dst, 16, 0, 0);
-#endif
 }
 
 // LDS reads of data that arrived by global_load_lds are written as asm, so that the
@@ -500,7 +486,7 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
   constexpr int kStages = 4, kAhead = kStages - 1;
   constexpr int UPW = D / 64;             // 1-KiB units of K (and of V) each wave fetches per tile
   constexpr int UPB = BLK_LDS / 1024;     // units per block
-  constexpr int NI = 2 * UPW * kDmaPerKiB;  // DMA instructions per wave per tile
+  constexpr int NI = 2 * UPW;             // DMA instructions per wave per tile
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, half = lane >> 5, c32 = lane & 31;
@@ -668,13 +654,6 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
   // the S(u+1) products and the exponentials of S(u), which are independent, sit in one
   // block and are interleaved: the wave keeps issuing VALU work while each MFMA of the
   // dependent chain is in the pipe.
-  // The two waves of a SIMD (w and w + 4) take their once-per-tile hand-over at different
-  // points of the step: waves 0-3 between the S products and the O products, waves 4-7
-  // before the S products.  The barrier therefore releases them half a step apart, and
-  // while one wave of a SIMD is in its VALU-heavy half (exponentials interleaved with the
-  // S products) the other is in its MFMA-only half (O products), instead of both
-  // competing for the same unit.
-  const bool early_sync = CRONUS_SKEW && wave >= kWaves / 2;
   auto tile_sync = [&](int jn) {
     wait_vmcnt<NI>();
     __builtin_amdgcn_s_barrier();
@@ -683,7 +662,6 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
   };
   auto fast_step = [&](int u, f32x16& s_cur, f32x16& s_nxt, bool opens_tile) {
     const int jn = (u >> 1) + kAhead;
-    if (opens_tile && early_sync) tile_sync(jn);
     issue_v(u);              // lands during the block below
     lds_land<NSTEP>(ka);     // K(u+1), issued before the previous step's O products
     qk(s_nxt);
@@ -704,7 +682,7 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
     }
     l += tile_sum;
     if (opens_tile) {
-      if (!early_sync) tile_sync(jn);
+      tile_sync(jn);
     } else if constexpr (UPW > 1) {
       issue_part(jn, 2);
       issue_part(jn, 3);
