@@ -117,9 +117,12 @@ int cronus_kv_append(const cronus_kv_cache* cache, const void* k_src, const void
  *   block_tables : device, int32 [n_seqs][max_blocks_per_seq]
  *   sm_scale     : softmax scale, normally 1/sqrt(D)
  *   workspace    : device, at least cronus_attn_mixed_workspace_bytes() bytes, 256-byte
- *                  aligned; holds the work list and split partial results; contents
- *                  are undefined afterwards; must not be shared by calls that can
- *                  overlap on the device
+ *                  aligned; holds the partial results of key spans until they are
+ *                  merged; contents are undefined afterwards; must not be shared by
+ *                  calls that can overlap on the device
+ * The work list is built on the host during the call and read by the kernels from
+ * pinned, device-mapped host memory that the library owns (a ring of 8 buffers, grown on
+ * demand, never freed; the ninth call in flight waits on the host for the first).
  * Errors: INVALID_ARG (null pointers, negative lengths, prefix+chunk >
  * 16*max_blocks_per_seq), UNSUPPORTED, WORKSPACE, HIP.
  */

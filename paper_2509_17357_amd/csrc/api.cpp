@@ -52,10 +52,14 @@ int device_cus() {
   return cached;
 }
 
-// Pinned host staging for the work list: the copy to the workspace is then a true
-// stream-ordered asynchronous copy.  A slot is reused only after its copy finished.
+// The work list is written into pinned, device-mapped host memory and the kernels read it
+// from there (each work-group one 64-byte item; the merge kernel its record): no copy
+// sits between the caller's previous work on the stream and the attention kernel (a
+// stream-ordered copy of these few KB took about 25 us of otherwise idle stream time on
+// MI355X).  A slot is reused only after the kernels of the call that used it finished.
 struct Slot {
   void* host = nullptr;
+  void* dev = nullptr;   // the same memory as the device sees it
   size_t cap = 0;
   hipEvent_t done = nullptr;
   bool pending = false;
@@ -77,11 +81,16 @@ Slot* acquire_slot(size_t bytes) {
   }
   if (s->cap < bytes) {
     if (s->host) (void)hipHostFree(s->host);
-    s->host = nullptr;
+    s->host = s->dev = nullptr;
     s->cap = 0;
     size_t cap = 1 << 16;
     while (cap < bytes) cap <<= 1;
-    if (hipHostMalloc(&s->host, cap, hipHostMallocDefault) != hipSuccess) return nullptr;
+    if (hipHostMalloc(&s->host, cap, hipHostMallocMapped) != hipSuccess) return nullptr;
+    if (hipHostGetDevicePointer(&s->dev, s->host, 0) != hipSuccess) {
+      (void)hipHostFree(s->host);
+      s->host = nullptr;
+      return nullptr;
+    }
     s->cap = cap;
   }
   if (!s->done && hipEventCreateWithFlags(&s->done, hipEventDisableTiming) != hipSuccess) return nullptr;
@@ -183,19 +192,17 @@ int cronus_attn_mixed(const cronus_kv_cache* cache, const void* q, void* out, co
   if (plan.n_items > 0x7fffffffLL) return CRONUS_ERR_INVALID_ARG;
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  {
-    std::lock_guard<std::mutex> lock(g_mu);
-    Slot* slot = acquire_slot(plan.upload_bytes);
-    if (!slot) return CRONUS_ERR_HIP;
-    write_plan(&plan, slot->host);
-    if (hipMemcpyAsync(workspace, slot->host, plan.upload_bytes, hipMemcpyHostToDevice, stream) != hipSuccess)
-      return CRONUS_ERR_HIP;
-    if (hipEventRecord(slot->done, stream) != hipSuccess) return CRONUS_ERR_HIP;
-    slot->pending = true;
-  }
-  AttnLaunch a{cache, q, out, block_tables, max_blocks_per_seq, sm_scale, workspace, &plan, hip_stream,
+  std::lock_guard<std::mutex> lock(g_mu);
+  Slot* slot = acquire_slot(plan.upload_bytes);
+  if (!slot) return CRONUS_ERR_HIP;
+  write_plan(&plan, slot->host);
+  AttnLaunch a{cache, q, out, block_tables, max_blocks_per_seq, sm_scale, workspace, slot->dev, &plan, hip_stream,
                g_ev_start, g_ev_stop};
-  return launch_attn(a);
+  const int rc = launch_attn(a);
+  // whatever was launched may still read the slot
+  if (hipEventRecord(slot->done, stream) != hipSuccess) return CRONUS_ERR_HIP;
+  slot->pending = true;
+  return rc;
 }
 
 void cronus_profile_events(void* start_event, void* stop_event) {

@@ -1057,9 +1057,10 @@ int launch_attn(const AttnLaunch& a) {
   p.k_scale = c.k_scale;
   p.v_scale = c.v_scale;
   p.block_tables = a.block_tables;
-  p.seqs = reinterpret_cast<const SeqInfo*>(ws + pl.off_seqs);
-  p.items = reinterpret_cast<const WorkItem*>(ws + pl.off_items);
-  p.merges = reinterpret_cast<const MergeItem*>(ws + pl.off_merge);
+  const unsigned char* image = static_cast<const unsigned char*>(a.plan_image);
+  p.seqs = reinterpret_cast<const SeqInfo*>(image + pl.off_seqs);
+  p.items = reinterpret_cast<const WorkItem*>(image + pl.off_items);
+  p.merges = reinterpret_cast<const MergeItem*>(image + pl.off_merge);
   p.partials = reinterpret_cast<float*>(ws + pl.off_partials);
   p.max_blocks = a.max_blocks_per_seq;
   p.n_q_heads = c.num_q_heads;

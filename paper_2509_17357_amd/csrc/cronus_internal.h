@@ -93,7 +93,8 @@ struct AttnLaunch {
   const int32_t* block_tables;
   int32_t max_blocks_per_seq;
   float sm_scale;
-  void* workspace;  // device; metadata already uploaded
+  void* workspace;  // device; holds the partial results at plan->off_partials
+  const void* plan_image;  // device-visible [SeqInfo | WorkItem | MergeItem] image at the plan's offsets
   const Plan* plan;
   void* stream;
   void* ev_start;  // optional hipEvent_t pair recorded around the main kernel
