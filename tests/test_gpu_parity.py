@@ -51,6 +51,8 @@ RAGGED = [
     (16, 2, 128, [77, 300], [9, 1]),                 # G = 8
     (28, 4, 128, [10, 129, 0], [50, 1, 260]),        # G = 7 (Qwen2-7B-like grouping)
     (8, 8, 64, [0], [1]),                            # a single key
+    (64, 1, 128, [33, 200], [40, 1]),                # G = 64 > 32: two head groups per KV head
+    (8, 1, 64, [100, 5, 900], [70, 1, 1]),           # multi-query attention, D = 64
 ]
 
 
@@ -122,6 +124,11 @@ def test_very_long_decode_context():
 
 def test_config2_scaled_down():
     U.assert_within_tolerance(run_batch(W.draw_batch(2, scale=0.25)))
+
+
+def test_fp8_cache_head_dim_64():
+    batch = W.custom_batch(W.HeadShape(8, 2, 64, "fp8"), [300, 20, 1500], [140, 1, 1], seed=4410)
+    U.assert_within_tolerance(run_batch(batch))
 
 
 def test_fp8_cache_small():
