@@ -221,6 +221,6 @@ const char* cronus_status_string(int status) {
   }
 }
 
-int cronus_version(void) { return 100; }
+int cronus_version(void) { return 200; }  // 0.2.0: + cronus_kv_gather, cronus_balancer_split
 
 }  // extern "C"
