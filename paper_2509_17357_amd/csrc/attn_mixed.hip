@@ -920,22 +920,26 @@ __device__ __forceinline__ void run_narrow(const AttnParams& p, const WorkItem& 
     }
   }
 
-  // combine the waves (each covered different keys) in wave 0: every wave parks its
-  // accumulators in its own LDS planes (its reads of them are complete)
+  // combine the waves (each covered different keys) pairwise, in log2(waves) rounds: a
+  // wave that is a source of the coming round parks its accumulators in its own LDS
+  // planes (its reads of them are complete), the wave kWaves/2, then /4, ... below it
+  // folds them into its own
   float* xo = reinterpret_cast<float*>(smem + wave * WAVE_LDS) + lane;        // [NACC][64]
   float* xs = reinterpret_cast<float*>(smem + kWaves * WAVE_LDS) + lane;      // [kWaves][2][64]
-  if (wave > 0) {
+  auto park = [&]() {
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
       for (int i = 0; i < 16; ++i) xo[(db * 16 + i) * 64] = o[db][i];
     xs[(wave * 2) * 64] = m;
     xs[(wave * 2 + 1) * 64] = l;
-  }
-  __syncthreads();
-  if (wave == 0) {
+  };
+  if (wave >= kWaves / 2) park();
 #pragma unroll 1
-    for (int w2 = 1; w2 < kWaves; ++w2) {
+  for (int n = kWaves / 2; n >= 1; n >>= 1) {
+    __syncthreads();
+    if (wave < n) {
+      const int w2 = wave + n;
       const float* w = reinterpret_cast<const float*>(smem + w2 * WAVE_LDS) + lane;
       const float mo = xs[(w2 * 2) * 64], lo = xs[(w2 * 2 + 1) * 64];
       const float mn = fmaxf(m, mo);
@@ -946,7 +950,10 @@ __device__ __forceinline__ void run_narrow(const AttnParams& p, const WorkItem& 
         for (int i = 0; i < 16; ++i) o[db][i] = o[db][i] * a0 + w[(db * 16 + i) * 64] * a1;
       l = l * a0 + lo * a1;
       m = mn;
+      if (2 * wave >= n) park();  // n/2 <= wave < n: a source of the next round
     }
+  }
+  if (wave == 0) {
     float lt = pair_sum(l);
     if (c32 < rows_valid) {
       if (it.partial < 0) {
