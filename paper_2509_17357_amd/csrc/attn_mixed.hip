@@ -2,15 +2,18 @@
 // chunked prefill instance batches a continuation chunk with decodes; Eq. 3 names
 // the two attention terms).  One launch runs every work item of the batch:
 //   wide item   - a tile of 256 chunk rows (tokens x the q heads of one KV head) against
-//                 keys 0 .. its causal limit; K/V blocks are staged through LDS and
+//                 keys 0 .. its causal limit, or against one span of them when the
+//                 planner cut a long tile; K/V blocks are staged through LDS and
 //                 shared by the 8 waves, each wave owning 32 rows.  For a bf16 cache
-//                 the blocks arrive by global->LDS DMA four tiles deep and the two
-//                 waves of every SIMD alternate between an MFMA phase and a softmax
-//                 phase (ping-pong, one s_barrier per phase).
+//                 the blocks arrive by global->LDS DMA through a ring of four 64-key
+//                 tiles, three tiles ahead; the waves run freely between one s_barrier
+//                 per tile, so the two waves of a SIMD fill each other's MFMA and VALU
+//                 gaps.
 //   narrow item - at most 32 rows (a decode, or a short chunk) against a span of
 //                 keys; the 8 waves split the span and stream K/V chunks from the
-//                 paged pools; partial results of spans are combined by the merge
-//                 kernel.
+//                 paged pools through private LDS planes.
+// Items that cover a span only leave (O, m, l) partial results, which the merge kernel
+// combines.
 //
 // Both compute S^T = K Q^T and O^T = V^T P^T with v_mfma_f32_32x32x16_bf16, so a
 // lane owns one query row (column of S^T): its softmax statistics are lane-local
