@@ -121,8 +121,9 @@ __device__ __forceinline__ u32x4 to_bf16_chunk(typename RawChunk<FP8>::type c) {
 // Online softmax update of one 32(q) x 32(key) S^T tile held as 16 accumulators per
 // lane.  key of accumulator i = sub_base + 16*(i/8) + 8*half + i%8.
 // Returns the two P^T operands (keys 0-15 and 16-31 of the sub-tile).
-// First part: causal mask, running maximum (rescales O and l when some row's maximum
-// grew).  Second part: numerators, their row sum, and the bf16 P^T operands.
+// First part: causal mask, running reference m (rescales O and l when some row's maximum
+// outgrew it by more than kLazyLog2 bits).  Second part: numerators, their row sum, and
+// the bf16 P^T operands.
 template <int NDB, bool FORCE = false>
 __device__ __forceinline__ void softmax_max_part(f32x16& s, bool need_mask, int sub_base, int half, int limit,
                                                  float c, float& m, float& l, f32x16 (&o)[NDB]) {
