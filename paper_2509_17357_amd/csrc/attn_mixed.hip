@@ -51,7 +51,6 @@ struct AttnParams {
   const float* k_scale;
   const float* v_scale;
   const int* block_tables;
-  const SeqInfo* seqs;
   const WorkItem* items;
   const MergeItem* merges;
   float* partials;
@@ -995,7 +994,6 @@ template <int D, bool FP8>
 __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(AttnParams p) {
   constexpr int TPR = D / 4, RPP = kMergeThreads / TPR;
   const MergeItem mi = p.merges[blockIdx.x];
-  const SeqInfo si = p.seqs[mi.seq];
   const int dq = threadIdx.x % TPR;
   const size_t slot = (size_t)kNarrowRows * (D + 2);
   const size_t step = slot * (size_t)mi.stride;
@@ -1015,7 +1013,7 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(AttnParams p)
     }
     const int tr = mi.row0 + r;
     const int t = tr / mi.n_heads, gi = tr - t * mi.n_heads;
-    unsigned short* op = p.out + ((long long)(si.q_off + mi.q_tok0 + t) * p.n_q_heads + mi.head0 + gi) * D + 4 * dq;
+    unsigned short* op = p.out + ((long long)(mi.q_off + mi.q_tok0 + t) * p.n_q_heads + mi.head0 + gi) * D + 4 * dq;
     const float f = vmul / ls;
     u32x2 w2 = {pack_bf16(acc[0] * f, acc[1] * f), pack_bf16(acc[2] * f, acc[3] * f)};
     *reinterpret_cast<u32x2*>(op) = w2;
@@ -1069,7 +1067,6 @@ int launch_attn(const AttnLaunch& a) {
   p.v_scale = c.v_scale;
   p.block_tables = a.block_tables;
   const unsigned char* image = static_cast<const unsigned char*>(a.plan_image);
-  p.seqs = reinterpret_cast<const SeqInfo*>(image + pl.off_seqs);
   p.items = reinterpret_cast<const WorkItem*>(image + pl.off_items);
   p.merges = reinterpret_cast<const MergeItem*>(image + pl.off_merge);
   p.partials = reinterpret_cast<float*>(ws + pl.off_partials);

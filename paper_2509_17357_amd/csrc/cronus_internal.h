@@ -60,7 +60,7 @@ struct MergeItem {
   int32_t row0;
   int32_t n_rows;
   int32_t stride;
-  int32_t pad0;
+  int32_t q_off;  // the sequence's first row in q/out (copy of SeqInfo::q_off: one dependent load less)
 };
 
 struct Plan {
@@ -69,7 +69,7 @@ struct Plan {
   int32_t n_seqs = 0;
   int32_t wide_rows = 0;  // rows per wide tile (compile-time choice of the kernel instance)
   // byte offsets inside the workspace
-  size_t off_seqs = 0, off_items = 0, off_merge = 0, off_partials = 0, total_bytes = 0;
+  size_t off_items = 0, off_merge = 0, off_partials = 0, total_bytes = 0;
   size_t upload_bytes = 0;  // [0, upload_bytes) is host-built metadata
 };
 
@@ -94,7 +94,7 @@ struct AttnLaunch {
   int32_t max_blocks_per_seq;
   float sm_scale;
   void* workspace;  // device; holds the partial results at plan->off_partials
-  const void* plan_image;  // device-visible [SeqInfo | WorkItem | MergeItem] image at the plan's offsets
+  const void* plan_image;  // device-visible [WorkItem | MergeItem] image at the plan's offsets
   const Plan* plan;
   void* stream;
   void* ev_start;  // optional hipEvent_t pair recorded around the main kernel

@@ -285,8 +285,7 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
   plan->n_partials = n_partials;
   plan->n_merge = (int64_t)sc.merges.size();
   plan->n_merge_rows = n_merge_rows;
-  plan->off_seqs = 0;
-  plan->off_items = align_up(plan->off_seqs + sizeof(SeqInfo) * (size_t)n_seqs, 256);
+  plan->off_items = 0;
   plan->off_merge = align_up(plan->off_items + sizeof(WorkItem) * n_slots, 256);
   plan->upload_bytes = align_up(plan->off_merge + sizeof(MergeItem) * sc.merges.size(), 256);
   plan->off_partials = plan->upload_bytes;
@@ -299,10 +298,9 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
 void write_plan(const Plan* plan, void* host_buf) {
   // copies the work list that the last build_plan() of this thread left in its scratch
   Scratch& sc = scratch();
-  const int32_t n_seqs = plan->n_seqs;
   const size_t n_slots = (size_t)plan->n_items;
   unsigned char* h = static_cast<unsigned char*>(host_buf);
-  if (n_seqs) std::memcpy(h + plan->off_seqs, sc.seqs.data(), sizeof(SeqInfo) * (size_t)n_seqs);
+  // (the per-sequence records travel inside the work and merge items; the kernels read nothing else)
   WorkItem* wi = reinterpret_cast<WorkItem*>(h + plan->off_items);
   WorkItem idle{};
   idle.wide = -1;
@@ -322,7 +320,10 @@ void write_plan(const Plan* plan, void* host_buf) {
       wi[i] = idle;
     }
   }
-  if (!sc.merges.empty()) std::memcpy(h + plan->off_merge, sc.merges.data(), sizeof(MergeItem) * sc.merges.size());
+  if (!sc.merges.empty()) {
+    for (MergeItem& mi : sc.merges) mi.q_off = sc.seqs[(size_t)mi.seq].q_off;
+    std::memcpy(h + plan->off_merge, sc.merges.data(), sizeof(MergeItem) * sc.merges.size());
+  }
 }
 
 }  // namespace cronus
