@@ -88,6 +88,7 @@ def time_workload(name, steps, warmup, trial=0):
     res = {
         "workload": name,
         "tokens_per_s": batch.total_q / (ms_per_step * 1e-3),
+        "kv_tokens_per_s": int(batch.kv_lens.sum()) / (ms_per_step * 1e-3),
         "ms_per_step": ms_per_step,
         "attn_kernel_ms": kernel_ms,
         "attn_kernel_ms_min": float(np.min(kern_ms)),
