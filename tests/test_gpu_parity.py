@@ -122,6 +122,51 @@ def test_very_long_decode_context():
     U.assert_within_tolerance(run_batch(batch))
 
 
+SHAPES = [W.HeadShape(32, 8, 128), W.HeadShape(8, 2, 64), W.HeadShape(28, 4, 128), W.HeadShape(16, 16, 64),
+          W.HeadShape(8, 1, 128), W.HeadShape(16, 2, 128, "fp8"), W.HeadShape(8, 4, 64, "fp8")]
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_small_batches(seed):
+    """Seeded random mixes of prompts without prefix, continuation chunks of every size class
+    (a few tokens, part of a tile, several tiles) and decodes, over several head shapes: the
+    planner's thresholds (narrow / wide, spans, interleaving) are hit in combinations that
+    the hand-written cases do not list."""
+    rng = np.random.default_rng(97000 + seed)
+    shape = SHAPES[seed % len(SHAPES)]
+    n = int(rng.integers(1, 13))
+    P, C = [], []
+    for _ in range(n):
+        kind = rng.integers(0, 5)
+        if kind == 0:      # decode
+            P.append(int(rng.integers(0, 4000))); C.append(1)
+        elif kind == 1:    # short chunk (narrow item)
+            P.append(int(rng.integers(0, 2500))); C.append(int(rng.integers(2, 9)))
+        elif kind == 2:    # part of a tile
+            P.append(int(rng.integers(0, 3000))); C.append(int(rng.integers(9, 70)))
+        elif kind == 3:    # several tiles
+            P.append(int(rng.integers(0, 2000))); C.append(int(rng.integers(70, 400)))
+        else:              # prompt without prefix
+            P.append(0); C.append(int(rng.integers(1, 300)))
+    batch = W.custom_batch(shape, P, C, seed=97000 + seed)
+    U.assert_within_tolerance(run_batch(batch))
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_long_context_batches(seed):
+    """Few chunks against long prefixes (their wide tiles are cut into key spans and merged)
+    next to decodes of very different lengths (spans, merges, interleaved queues)."""
+    rng = np.random.default_rng(98000 + seed)
+    shape = [W.SHAPE_8B, W.HeadShape(28, 4, 128), W.HeadShape(16, 2, 128, "fp8"), W.HeadShape(8, 2, 64)][seed % 4]
+    P = [int(rng.integers(2000, 24000)) for _ in range(int(rng.integers(1, 4)))]
+    C = [int(rng.integers(64, 512)) for _ in P]
+    n_dec = int(rng.integers(0, 21))
+    P += [int(rng.integers(100, 20000)) for _ in range(n_dec)]
+    C += [1] * n_dec
+    batch = W.custom_batch(shape, P, C, seed=98000 + seed)
+    U.assert_within_tolerance(run_batch(batch))
+
+
 def test_config2_scaled_down():
     U.assert_within_tolerance(run_batch(W.draw_batch(2, scale=0.25)))
 
