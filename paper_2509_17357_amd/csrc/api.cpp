@@ -85,7 +85,7 @@ Slot* acquire_slot(size_t bytes) {
     s->cap = 0;
     size_t cap = 1 << 16;
     while (cap < bytes) cap <<= 1;
-    if (hipHostMalloc(&s->host, cap, hipHostMallocMapped) != hipSuccess) return nullptr;
+    if (hipHostMalloc(&s->host, cap, hipHostMallocMapped | hipHostMallocPortable) != hipSuccess) return nullptr;
     if (hipHostGetDevicePointer(&s->dev, s->host, 0) != hipSuccess) {
       (void)hipHostFree(s->host);
       s->host = nullptr;
