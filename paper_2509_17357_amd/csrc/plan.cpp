@@ -232,7 +232,7 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
     }
   }
   // Where decode spans are a large part of a queue's work but not nearly all of it (estimated
-  // time at least half of its wide tiles' and at most five times theirs), the two kinds alternate in proportion to their estimated times, each
+  // time at least 0.3 of its wide tiles' and at most ten times theirs), the two kinds alternate in proportion to their estimated times, each
   // kind keeping its order: while some CUs of the XCD compute wide tiles (little HBM
   // traffic), the others stream decode spans, and a CU that streams next to computing CUs
   // gets a larger share of the memory system than one that streams next to 255 others.
@@ -243,13 +243,15 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
   // of the queue anyway.
   constexpr double kWideLead = 0.75;
   for (auto& q : sc.queue) {
-    auto time_of = [&](int32_t ref) {  // microseconds, from measurements on MI355X
+    // microseconds per item, fitted to per-work-group timestamps of the Llama-3-8B-shaped
+    // batch on MI355X (D = 128, bf16; only the ratio of the two kinds matters here)
+    auto time_of = [&](int32_t ref) {
       if (ref >= 0) {
         const WorkItem& w = sc.wide[(size_t)ref];
-        return 9.0 + (w.kv_end - w.kv_begin) / 32.0;
+        return 5.0 + 0.0286 * (w.kv_end - w.kv_begin);
       }
       const WorkItem& w = sc.narrow[(size_t)~ref];
-      return 0.5 * (6.0 + 0.026 * (w.kv_end - w.kv_begin));
+      return 9.6 + 0.0141 * (w.kv_end - w.kv_begin);
     };
     double total[2] = {0, 0}, done[2] = {0, 0};
     size_t n_wide_q = 0;
@@ -257,7 +259,7 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
       total[ref < 0] += time_of(ref);
       n_wide_q += ref >= 0;
     }
-    if (n_wide_q == 0 || n_wide_q == q.size() || total[1] < 0.25 * total[0] || total[0] < 0.1 * total[1]) continue;
+    if (n_wide_q == 0 || n_wide_q == q.size() || total[1] < 0.3 * total[0] || total[0] < 0.1 * total[1]) continue;
     sc.order.assign(q.begin(), q.end());  // wide refs first, then narrow refs
     size_t iw = 0, in = n_wide_q, k = 0;
     while (iw < n_wide_q || in < sc.order.size()) {
