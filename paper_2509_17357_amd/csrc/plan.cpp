@@ -190,9 +190,14 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
   // (wide = -1).
   double load[kXcds] = {0};
   for (auto& q : sc.queue) q.clear();
+  // Given equal work, the odd-numbered XCDs of an MI355X finished 2-5 % later than the
+  // even-numbered ones in every per-work-group trace taken (HBM-bound and MFMA-bound
+  // launches alike), so their load counts a little more when work is dealt out.
+  constexpr double kOddXcdWeight = 1.03;
+  auto weighted = [&](int x) { return load[x] * ((x & 1) ? kOddXcdWeight : 1.0); };
   auto least_loaded = [&]() {
     int x = 0;
-    for (int i = 1; i < kXcds; ++i) if (load[i] < load[x]) x = i;
+    for (int i = 1; i < kXcds; ++i) if (weighted(i) < weighted(x)) x = i;
     return x;
   };
   std::sort(sc.groups.begin(), sc.groups.end(), [](const Group& a, const Group& b) { return a.cost > b.cost; });
