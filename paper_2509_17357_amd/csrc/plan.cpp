@@ -190,14 +190,14 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
   // (wide = -1).
   double load[kXcds] = {0};
   for (auto& q : sc.queue) q.clear();
-  // Given equal work, the odd-numbered XCDs of an MI355X finished 2-5 % later than the
-  // even-numbered ones in every per-work-group trace taken (HBM-bound and MFMA-bound
-  // launches alike), so their load counts a little more when work is dealt out.
-  constexpr double kOddXcdWeight = 1.03;
-  auto weighted = [&](int x) { return load[x] * ((x & 1) ? kOddXcdWeight : 1.0); };
+  // Given equal work, the odd-numbered XCDs of an MI355X finished later than the
+  // even-numbered ones in every per-work-group trace taken: about 3 % on wide tiles
+  // (MFMA-bound), about 6 % on decode spans (HBM-bound).  Work dealt to an odd XCD is
+  // therefore booked that much heavier.
+  constexpr double kOddXcdWide = 1.03, kOddXcdNarrow = 1.06;
   auto least_loaded = [&]() {
     int x = 0;
-    for (int i = 1; i < kXcds; ++i) if (weighted(i) < weighted(x)) x = i;
+    for (int i = 1; i < kXcds; ++i) if (load[i] < load[x]) x = i;
     return x;
   };
   std::sort(sc.groups.begin(), sc.groups.end(), [](const Group& a, const Group& b) { return a.cost > b.cost; });
@@ -214,7 +214,7 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
       const int x = least_loaded();
       for (int i = hi - 1; i >= lo; --i) {
         sc.queue[x].push_back(i);
-        load[x] += sc.wide_cost[(size_t)i];
+        load[x] += sc.wide_cost[(size_t)i] * ((x & 1) ? kOddXcdWide : 1.0);
       }
     }
   }
@@ -233,7 +233,7 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
       const WorkItem& w = sc.narrow[(size_t)i];
       const int x = least_loaded();
       sc.queue[x].push_back(~i);
-      load[x] += 0.5 * (w.kv_end - w.kv_begin);
+      load[x] += 0.5 * (w.kv_end - w.kv_begin) * ((x & 1) ? kOddXcdNarrow : 1.0);
     }
   }
   // Where decode spans are a large part of a queue's work but not nearly all of it (estimated
