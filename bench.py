@@ -209,8 +209,10 @@ def cpu_baseline(batch, budget_s=12.0, min_s=10.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    # defaults: the clocks of an idle MI355X take some tens of milliseconds of work to settle
+    # (10 warm-up steps of this 0.2 ms step measured 9 % slower than 100)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default="llama3_8b", choices=sorted(WORKLOADS))
     ap.add_argument("--no-extra", action="store_true", help="skip the prefill-heavy / decode-heavy runs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -244,7 +246,7 @@ def main():
             if name != args.workload:
                 others[name], _ = time_workload(name, max(5, args.steps // 2), max(2, args.warmup // 2))
         if args.workload != "llama_70b_fp8":
-            others["llama_70b_fp8"], _ = time_workload("llama_70b_fp8", 5, 2)
+            others["llama_70b_fp8"], _ = time_workload("llama_70b_fp8", max(5, args.steps // 10), max(2, args.warmup // 10))
         scatter_gather = time_scatter_gather()
     sh = batch.shape
     line = {
