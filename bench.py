@@ -30,6 +30,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 WORKLOADS = {"tiny": 1, "llama3_8b": 2, "prefill_heavy": 3, "decode_heavy": 4, "llama_70b_fp8": 5}
+CLOCK_SETTLE_MS = 60.0         # untimed work before the warm-up steps: clocks of an idle GPU rise over tens of ms
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 # which roofline bounds the attention kernel on each workload (KV bytes vs visible-pair flops)
@@ -56,6 +57,12 @@ def time_workload(name, steps, warmup, trial=0):
     it.ensure_workspace()
     torch.cuda.synchronize()
 
+    # let the clocks of an idle GPU settle (untimed, not counted as warm-up steps), then the W warm-up steps
+    t_settle = time.perf_counter()
+    while (time.perf_counter() - t_settle) * 1e3 < CLOCK_SETTLE_MS:
+        for _ in range(8):
+            it.step()
+        torch.cuda.synchronize()
     for _ in range(warmup):
         it.step()
     torch.cuda.synchronize()
@@ -262,6 +269,7 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
+        "clock_settle_ms": CLOCK_SETTLE_MS,
         "config": {"workload": args.workload, "q_heads": sh.n_q_heads, "kv_heads": sh.n_kv_heads,
                    "head_dim": sh.head_dim, "kv_dtype": sh.kv_dtype, "block_size": 16,
                    "n_seqs": batch.n_seqs, "q_tokens": batch.total_q, "kv_tokens": int(batch.kv_lens.sum()),
