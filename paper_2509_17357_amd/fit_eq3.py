@@ -96,6 +96,8 @@ def main():
         print("fit_eq3: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(2)
     from . import workloads as W
+    # let the clocks of an idle GPU settle before the first sample (untimed)
+    time_batch(make_batch(W, 8192, 64, 262144, args.budget, seed=8999), 200, 50)
     rows = []
     for i, (lp, nd, tot) in enumerate(sample_grid(args.budget)):
         batch = make_batch(W, lp, nd, tot, args.budget, seed=9000 + i)
