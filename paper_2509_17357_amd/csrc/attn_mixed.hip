@@ -22,12 +22,9 @@
 // the 8-key chunks the P^T operand needs; the same permutation on the V^T operand
 // rows makes each lane own 8 consecutive output dims.
 #include <hip/hip_runtime.h>
+#include <type_traits>
 
 #include "cronus_internal.h"
-
-#ifndef CRONUS_HINT
-#define CRONUS_HINT 7  // VALU instructions issued per MFMA in the interleaved block
-#endif
 
 namespace cronus {
 namespace {
@@ -435,30 +432,10 @@ __device__ __forceinline__ void lds_read8(u32x4 (&x)[8], unsigned addr) {
       : "memory");
 }
 
-// Split form for the steady-state loop: issue the reads, do independent work, then land
-// them.  `lds_land` names the destination registers as in-out operands of the wait, so
-// every later use of them depends on the wait; N = LDS reads issued after these that may
-// still be outstanding (LDS reads return in order).
-template <int O0, int O1, int O2, int O3>
-__device__ __forceinline__ void lds_issue4(u32x4 (&x)[4], unsigned addr) {
-  asm volatile(
-      "ds_read_b128 %0, %4 offset:%5\n\tds_read_b128 %1, %4 offset:%6\n\t"
-      "ds_read_b128 %2, %4 offset:%7\n\tds_read_b128 %3, %4 offset:%8"
-      : "=&v"(x[0]), "=&v"(x[1]), "=&v"(x[2]), "=&v"(x[3])
-      : "v"(addr), "i"(O0), "i"(O1), "i"(O2), "i"(O3)
-      : "memory");
-}
-template <int O0, int O1, int O2, int O3, int O4, int O5, int O6, int O7>
-__device__ __forceinline__ void lds_issue8(u32x4 (&x)[8], unsigned addr) {
-  asm volatile(
-      "ds_read_b128 %0, %8 offset:%9\n\tds_read_b128 %1, %8 offset:%10\n\t"
-      "ds_read_b128 %2, %8 offset:%11\n\tds_read_b128 %3, %8 offset:%12\n\t"
-      "ds_read_b128 %4, %8 offset:%13\n\tds_read_b128 %5, %8 offset:%14\n\t"
-      "ds_read_b128 %6, %8 offset:%15\n\tds_read_b128 %7, %8 offset:%16"
-      : "=&v"(x[0]), "=&v"(x[1]), "=&v"(x[2]), "=&v"(x[3]), "=&v"(x[4]), "=&v"(x[5]), "=&v"(x[6]), "=&v"(x[7])
-      : "v"(addr), "i"(O0), "i"(O1), "i"(O2), "i"(O3), "i"(O4), "i"(O5), "i"(O6), "i"(O7)
-      : "memory");
-}
+// Split form for the steady-state loop: a read is issued (`lds_issue1`), independent work
+// follows, and a wait lands it.  The waits name the destination registers as in-out
+// operands, so every later use of them depends on the wait; N = LDS reads issued after
+// these that may still be outstanding (LDS reads return in order).
 template <int N>
 __device__ __forceinline__ void lds_land(u32x4 (&x)[4]) {
   asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]) : "i"(N) : "memory");
@@ -469,6 +446,24 @@ __device__ __forceinline__ void lds_land(u32x4 (&x)[8]) {
                : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7])
                : "i"(N)
                : "memory");
+}
+
+// One read, and the wait that lands one register: the steady-state loop issues one read
+// in front of every MFMA instead of eight in a burst.
+template <int OFF>
+__device__ __forceinline__ void lds_issue1(u32x4& x, unsigned addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(x) : "v"(addr), "i"(OFF) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void lds_land1(u32x4& x) {
+  asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(x) : "i"(N) : "memory");
+}
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
 }
 
 // Schedule per wave (n = number of 32-key sub-tiles, S(u) = K(u) Q^T, P(u) = softmax
@@ -581,17 +576,6 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
       lds_read8<0, 512, 1024, 1536, BLK_LDS, BLK_LDS + 512, BLK_LDS + 1024, BLK_LDS + 1536>(va, a);
     else lds_read4<0, 512, BLK_LDS, BLK_LDS + 512>(va[0], va[1], va[2], va[3], a);
   };
-  auto issue_k = [&](int u) {
-    const unsigned a = k_lane + ((u >> 1) % kStages) * STAGE + (u & 1) * 2 * BLK_LDS;
-    if constexpr (NSTEP == 8) lds_issue8<0, 512, 1024, 1536, 2048, 2560, 3072, 3584>(ka, a);
-    else lds_issue4<0, 512, 1024, 1536>(ka, a);
-  };
-  auto issue_v = [&](int u) {
-    const unsigned a = v_lane + ((u >> 1) % kStages) * STAGE + (u & 1) * 2 * BLK_LDS;
-    if constexpr (NSTEP == 8)
-      lds_issue8<0, 512, 1024, 1536, BLK_LDS, BLK_LDS + 512, BLK_LDS + 1024, BLK_LDS + 1536>(va, a);
-    else lds_issue4<0, 512, BLK_LDS, BLK_LDS + 512>(va, a);
-  };
   auto active = [&](int u) { return 32 * u <= wave_max_limit; };
 
   u32x4 pp[2];
@@ -653,10 +637,13 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
     }
   };
   // Steady state: sub-tiles that this wave sees whole (no causal mask, no tail) and that
-  // are followed by two more.  No conditionals besides the once-per-tile hand-over, so
-  // the S(u+1) products and the exponentials of S(u), which are independent, sit in one
-  // block and are interleaved: the wave keeps issuing VALU work while each MFMA of the
-  // dependent chain is in the pipe.
+  // are followed by two more.  No conditionals besides the once-per-tile hand-over.  The
+  // instruction order is fixed by hand (a scheduling barrier closes every MFMA slot; the
+  // compiler's own interleaving hints left the S(u+1) chain in one clump): each of the
+  // NSTEP slots of the first block holds one LDS read of V(u), the MFMA of the S(u+1)
+  // chain and the numerators of S(u) that go with it; each slot of the second block one
+  // LDS read of K(u+2) and one O product.  An operand is thus requested NSTEP MFMA slots
+  // before its use, and LDS sees single reads, not bursts of eight per wave.
   auto tile_sync = [&](int jn) {
     wait_vmcnt<NI>();
     __builtin_amdgcn_s_barrier();
@@ -665,20 +652,41 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
   };
   auto fast_step = [&](int u, f32x16& s_cur, f32x16& s_nxt, bool opens_tile) {
     const int jn = (u >> 1) + kAhead;
-    issue_v(u);              // lands during the block below
-    lds_land<NSTEP>(ka);     // K(u+1), issued before the previous step's O products
-    qk(s_nxt);
-    // optimistic: numerators against the reference as it is; the row maxima are looked
-    // at only if some lane's sum shows that a score outgrew the reference (or it is the
-    // first sub-tile, whose reference is kNeg and whose numerators overflow)
-    float tile_sum = softmax_exp_part(s_cur, c, m, pp);
-#if CRONUS_HINT
+    const unsigned av = v_lane + ((u >> 1) % kStages) * STAGE + (u & 1) * 2 * BLK_LDS;
+    const unsigned ak = k_lane + (((u + 2) >> 1) % kStages) * STAGE + (u & 1) * 2 * BLK_LDS;
+    // On entry the NSTEP reads of K(u+1) are in flight or landed and nothing else is.
+    // Every MFMA slot issues one read and lands the operand it uses, which was issued
+    // NSTEP reads earlier: after the slot's own issue NSTEP + 1 reads can be outstanding,
+    // and waiting for all but NSTEP of them lands exactly the oldest.
+    // Optimistic numerators: against the reference as it is; the row maxima are looked at
+    // only if some lane's sum shows that a score outgrew the reference (or it is the first
+    // sub-tile, whose reference is kNeg and whose numerators overflow).
+    float tile_sum = 0.f;
+    {
+      const float mc = m * c;
+      const bf16x2_t ones = __builtin_bit_cast(bf16x2_t, 0x3f803f80u);
+      constexpr int PPM = 8 / NSTEP;  // numerator pairs per MFMA
 #pragma unroll
-    for (int i = 0; i < NSTEP; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x402, CRONUS_HINT, 0);
+      for (int i = 0; i < 16; ++i) s_nxt[i] = 0.f;
+      __builtin_amdgcn_sched_barrier(0);
+      static_for<0, NSTEP>([&](auto I) {
+        constexpr int st = decltype(I)::value;
+        lds_issue1<(st / NDB) * BLK_LDS + (st % NDB) * 512>(va[st], av);
+        lds_land1<NSTEP>(ka[st]);
+        s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ka[st]), qreg[st], s_nxt, 0, 0, 0);
+#pragma unroll
+        for (int x = 0; x < PPM; ++x) {
+          const int pr = st * PPM + x;
+          const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[2 * pr], c, -mc));
+          const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[2 * pr + 1], c, -mc));
+          const f32x2 e = {e0, e1};
+          const bf16x2_t pk = __builtin_convertvector(e, bf16x2_t);
+          pp[pr >> 2][pr & 3] = __builtin_bit_cast(unsigned int, pk);
+          tile_sum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, tile_sum, false);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      });
     }
-#endif
     if (__builtin_amdgcn_ballot_w64(!(tile_sum <= kTileSumLimit)) != 0) {
       softmax_max_part<NDB, true>(s_cur, false, 32 * u, half, limit, c, m, l, o);
       tile_sum = softmax_exp_part(s_cur, c, m, pp);
@@ -690,13 +698,14 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
       issue_part(jn, 2);
       issue_part(jn, 3);
     }
-    issue_k(u + 2);          // lands during the O products
-    lds_land<NSTEP>(va);     // V(u)
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int db = 0; db < NDB; ++db)
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va[t * NDB + db]), as_bf16x8(pp[t]), o[db], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<0, NSTEP>([&](auto I) {
+      constexpr int i = decltype(I)::value;
+      lds_issue1<i * 512>(ka[i], ak);
+      lds_land1<NSTEP>(va[i]);
+      o[i % NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va[i]), as_bf16x8(pp[i / NDB]), o[i % NDB], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    });
   };
   // sub-tile u is "whole" for this wave when u + 1 is too: 32 (u + 1) + 31 <= wave_min_limit
   int n_fast = wave_has_rows ? min(n_sub - 2, (wave_min_limit + 1) / 32 - 1) : 0;
