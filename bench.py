@@ -19,6 +19,7 @@ data movement.
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -74,12 +75,20 @@ def time_workload(name, steps, warmup, trial=0):
         it.attention()
     B.cronus_profile_events(None, None)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for a, b in pairs:
-        B.cronus_profile_events(a, b)
-        it.step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    # The interpreter's cyclic garbage collector stays out of the timed region: with torch
+    # imported one full collection takes 30-40 ms, twice the 100 timed steps of the default
+    # run, and whether one falls into them changed from run to run (0.18 or 0.5 ms/step).
+    gc.collect()
+    gc.disable()
+    try:
+        t0 = time.perf_counter()
+        for a, b in pairs:
+            B.cronus_profile_events(a, b)
+            it.step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    finally:
+        gc.enable()
     B.cronus_profile_events(None, None)
     kern_ms = [ev.elapsed_ms(a, b) for a, b in pairs]
     for a, b in pairs:
