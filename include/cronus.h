@@ -222,9 +222,10 @@ int cronus_balancer_split(const cronus_balancer_model* model, int64_t l_in, int6
 /*
  * cronus_profile_events - measurement aid.  While both handles (hipEvent_t cast to
  * void*, created by the caller with timing enabled) are set, every cronus_attn_mixed
- * records `start` immediately before and `stop` immediately after its main attention
- * kernel, on that call's stream; hipEventElapsedTime(start, stop) is then the duration
- * of that one kernel launch.  Pass NULL, NULL to switch it off (the default).
+ * launches its main attention kernel with them as the start and stop events of that
+ * dispatch (hipExtLaunchKernel), on that call's stream; hipEventElapsedTime(start, stop)
+ * is then the duration of that one kernel launch (within a few microseconds of what a
+ * profiler's kernel trace shows for it).  Pass NULL, NULL to switch it off (the default).
  * Process-wide; not meant for concurrent callers.
  */
 void cronus_profile_events(void* start_event, void* stop_event);

@@ -21,7 +21,9 @@
 // (perm32) so that the accumulators a lane holds after S^T are, in order, exactly
 // the 8-key chunks the P^T operand needs; the same permutation on the V^T operand
 // rows makes each lane own 8 consecutive output dims.
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
+
 #include <type_traits>
 
 #include "cronus_internal.h"
@@ -1046,11 +1048,15 @@ int launch_typed(const AttnLaunch& a, const AttnParams& p) {
         return CRONUS_ERR_HIP;
       attr_set = true;
     }
-    const bool timed = a.ev_start && a.ev_stop;
-    if (timed && hipEventRecord(static_cast<hipEvent_t>(a.ev_start), s) != hipSuccess) return CRONUS_ERR_HIP;
-    hipLaunchKernelGGL(kern, dim3((unsigned)pl.n_items), dim3(kThreads), lds, s, p);
+    if (a.ev_start && a.ev_stop) {
+      // the events take the begin and end time stamps of this dispatch itself, so their
+      // difference is the kernel's duration without the launch latency around it
+      hipExtLaunchKernelGGL(kern, dim3((unsigned)pl.n_items), dim3(kThreads), lds, s,
+                            static_cast<hipEvent_t>(a.ev_start), static_cast<hipEvent_t>(a.ev_stop), 0, p);
+    } else {
+      hipLaunchKernelGGL(kern, dim3((unsigned)pl.n_items), dim3(kThreads), lds, s, p);
+    }
     if (hipGetLastError() != hipSuccess) return CRONUS_ERR_HIP;
-    if (timed && hipEventRecord(static_cast<hipEvent_t>(a.ev_stop), s) != hipSuccess) return CRONUS_ERR_HIP;
   }
   if (pl.n_merge > 0) {
     hipLaunchKernelGGL((attn_merge_kernel<D, FP8>), dim3((unsigned)pl.n_merge), dim3(kMergeThreads), 0, s, p);
