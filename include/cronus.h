@@ -149,9 +149,12 @@ int cronus_attn_mixed_plan_stats(const cronus_kv_cache* cache, const int32_t* pr
  * cronus_attn_mixed_plan_items - the work list itself, for inspection and tests (host
  * only, nothing is launched).  Writes up to `capacity` items, 12 int32 each, in grid
  * order: seq, kv_head, head0, n_heads, q_tok0, n_tok, kv_begin, kv_end, partial, wide,
- * 0, 0.  wide = 1: chunk tile (all keys [0, kv_end)); wide = 0: narrow item over keys
- * [kv_begin, kv_end), partial >= 0 when its result is merged with other spans; wide = -1:
- * idle slot.  Returns the number of items of the plan (which may exceed capacity), or
+ * pair_tok1, pair_ntok.  wide = 1: chunk tile over keys [kv_begin, kv_end); wide = 0:
+ * narrow item over keys [kv_begin, kv_end); partial >= 0 when the item's result is merged
+ * with other spans of the same rows; wide = -1: idle slot.  pair_tok1 > 0 (wide items of
+ * launches with many tiles per CU): the same work-group then also computes the earlier
+ * tile of pair_ntok tokens that starts at chunk token pair_tok1 - 1, against all keys up
+ * to that tile's causal end.  Returns the number of items of the plan (which may exceed capacity), or
  * a negative cronus_status on invalid arguments.  items may be NULL when capacity = 0.
  */
 int64_t cronus_attn_mixed_plan_items(const cronus_kv_cache* cache, const int32_t* prefix_lens,

@@ -203,11 +203,12 @@ def cronus_attn_mixed_plan_stats(cache: cronus_kv_cache, prefix_lens, chunk_lens
     return {"items": st[0], "wide_items": st[1], "partials": st[2], "merge_rows": st[3]}
 
 
-PLAN_ITEM_FIELDS = ("seq", "kv_head", "head0", "n_heads", "q_tok0", "n_tok", "kv_begin", "kv_end", "partial", "wide")
+PLAN_ITEM_FIELDS = ("seq", "kv_head", "head0", "n_heads", "q_tok0", "n_tok", "kv_begin", "kv_end", "partial", "wide",
+                    "pair_tok1", "pair_ntok")
 
 
 def cronus_attn_mixed_plan_items(cache: cronus_kv_cache, prefix_lens, chunk_lens) -> np.ndarray:
-    """The work list as an int32 array [n_items, 12] (columns: PLAN_ITEM_FIELDS, then two zeros)."""
+    """The work list as an int32 array [n_items, 12] (columns: PLAN_ITEM_FIELDS)."""
     p, pp = _host_i32(prefix_lens)
     c, cp = _host_i32(chunk_lens)
     n = lib().cronus_attn_mixed_plan_items(ctypes.byref(cache), pp, cp, int(p.size), None, 0)

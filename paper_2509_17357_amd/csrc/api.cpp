@@ -162,7 +162,7 @@ int64_t cronus_attn_mixed_plan_items(const cronus_kv_cache* cache, const int32_t
   for (int64_t i = 0; i < n; ++i) {
     const WorkItem& w = wi[i];
     const int32_t row[12] = {w.seq, w.kv_head, w.head0, w.n_heads, w.q_tok0, w.n_tok, w.kv_begin, w.kv_end,
-                             w.partial, w.wide, 0, 0};
+                             w.partial, w.wide, w.pair_tok1, w.pair_ntok};
     std::memcpy(items + 12 * i, row, sizeof(row));
   }
   return plan.n_items;

@@ -8,7 +8,9 @@
 //                 the blocks arrive by global->LDS DMA through a ring of four 64-key
 //                 tiles, three tiles ahead; the waves run freely between one s_barrier
 //                 per tile, so the two waves of a SIMD fill each other's MFMA and VALU
-//                 gaps.
+//                 gaps.  An item may name a second, earlier tile of the same sequence and
+//                 KV head, which the work-group computes afterwards (whole prompts with
+//                 many tiles per CU: half as many work-group starts).
 //   narrow item - at most 32 rows (a decode, or a short chunk) against a span of
 //                 keys; the 8 waves split the span and stream K/V chunks from the
 //                 paged pools through private LDS planes.
@@ -989,8 +991,19 @@ __global__ __launch_bounds__(kThreads) void attn_mixed_kernel(AttnParams p) {
   const WorkItem it = p.items[blockIdx.x];
   if (it.wide < 0 || it.n_tok <= 0 || it.n_heads <= 0) return;  // idle slot that keeps the XCD queues aligned
   if (it.wide) {
-    if constexpr (FP8) run_wide_staged<D, FP8, 1>(p, it, smem);
-    else run_wide_dma<D>(p, it, smem);
+    // the tile itself, then the earlier tile paired with it (if any): keys from 0, final output
+    WorkItem cur = it;
+    for (int rep = 0;; ++rep) {
+      if constexpr (FP8) run_wide_staged<D, FP8, 1>(p, cur, smem);
+      else run_wide_dma<D>(p, cur, smem);
+      if (rep || it.pair_tok1 <= 0) break;
+      cur.q_tok0 = it.pair_tok1 - 1;
+      cur.n_tok = it.pair_ntok;
+      cur.kv_begin = 0;
+      cur.kv_end = it.prefix_len + cur.q_tok0 + cur.n_tok;
+      cur.partial = -1;
+      __syncthreads();  // every wave is done with the first tile's LDS stages
+    }
   } else {
     run_narrow<D, FP8>(p, it, smem);
   }

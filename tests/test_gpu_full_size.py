@@ -53,6 +53,38 @@ def test_paper_shaped_iteration_long_context_every_row():
     U.assert_within_tolerance(rep)
 
 
+@pytest.mark.parametrize("kind", ["bf16", "fp8"])
+def test_whole_prompts_paired_tiles_every_row(kind):
+    """Whole prompts (prefix 0; the prefill that precedes the hand-over of section 4.2) with
+    16 tiles per CU: the planner gives each work-group an early and a late tile of one
+    (sequence, KV head).  Prompt lengths leave whole, nearly whole and tiny last tiles, and
+    odd tile counts (a single middle tile); every output row is checked."""
+    if kind == "bf16":
+        shape, C = W.SHAPE_8B, [4096, 4100, 4031, 4160, 3900, 4200, 4097, 4223, 1500]
+    else:
+        shape, C = W.SHAPE_70B, [4096, 4100, 4031, 4223, 720]
+    batch = W.custom_batch(shape, [0] * len(C), C, seed=4242)
+    it = DeviceIteration(batch, pool_fill=0x7FC1 if kind == "bf16" else 0x7F)
+    kv_bits = it.load_host_inputs()
+    ks = vs = None
+    if it.fp8:
+        ks, vs = it.amax_scales()
+        it.set_fp8_scales(ks, vs)
+    it.setup_decode_context()
+    it.step()
+    torch.cuda.synchronize()
+    items = B.cronus_attn_mixed_plan_items(it.cache, batch.prefix_lens, batch.chunk_lens)
+    F = {n: i for i, n in enumerate(B.PLAN_ITEM_FIELDS)}
+    wide = items[items[:, F["wide"]] == 1]
+    assert (wide[:, F["pair_tok1"]] > 0).sum() > 0.9 * len(wide)      # the paired path is what runs
+    assert (wide[:, F["pair_tok1"]] == 0).sum() > 0                    # and some single middle tiles
+    ref = U.oracle_attention(batch, bits_from_bf16_tensor(it.q), U.oracle_kv_values(batch, kv_bits, ks, vs),
+                             it.sm_scale)
+    rep = U.error_report(batch, bits_from_bf16_tensor(it.out), ref)
+    print(batch.name, kind, rep)
+    U.assert_within_tolerance(rep)
+
+
 def _sampled_check(cid, n_decode_samples, chunk_row_sample):
     batch = W.draw_batch(cid)
     sh = batch.shape

@@ -29,8 +29,17 @@ def check_plan(shape, P, C):
     assert (real[:, F["wide"]] == 1).sum() == stats["wide_items"]
     # coverage[s][head, token] = list of (kv_begin, kv_end, partial)
     cover = {}
+    tiles = []
     for it in real:
-        s, kvh, h0, nh, t0, nt, kb, ke, part, wide = (int(x) for x in it[:10])
+        s, kvh, h0, nh, t0, nt, kb, ke, part, wide, pair1, pair_nt = (int(x) for x in it[:12])
+        tiles.append((s, kvh, h0, nh, t0, nt, kb, ke, part, wide))
+        if pair1:
+            # the second tile of a work-group: earlier tokens of the same heads, whole, final
+            assert wide == 1 and part == -1 and kb == 0 and 0 <= pair1 - 1 < t0 and pair_nt * nh > 32
+            tiles.append((s, kvh, h0, nh, pair1 - 1, pair_nt, 0, int(P[s]) + pair1 - 1 + pair_nt, -1, 1))
+        else:
+            assert pair_nt == 0
+    for s, kvh, h0, nh, t0, nt, kb, ke, part, wide in tiles:
         assert 0 <= s < len(P) and C[s] > 0 and 0 <= kvh < shape.n_kv_heads
         assert h0 // G == kvh and (h0 + nh - 1) // G == kvh and nh >= 1   # heads of one KV head
         assert 0 <= t0 and nt >= 1 and t0 + nt <= C[s]
@@ -127,3 +136,32 @@ def test_few_long_wide_tiles_are_split_over_keys():
     items3, _ = plan_for(b.shape, b.prefix_lens, b.chunk_lens)
     w3 = items3[items3[:, F["wide"]] == 1]
     assert (w3[:, F["kv_begin"]] == 0).all() and (w3[:, F["partial"]] == -1).all()
+
+
+def test_many_tiles_per_cu_are_paired():
+    """Whole prompts (prefix 0) with 16 or more tiles per CU: a work-group takes the i-th and
+    the (n-1-i)-th tile of a (sequence, KV head), so the items of one sequence cost the same
+    and there are half as many; continuation chunks with 8 tiles per CU stay single."""
+    sh = W.HeadShape(32, 8, 128)
+    P, C = [0] * 8, [4096] * 8                      # 8 x 64 tiles x 8 KV heads = 4096 tiles, 16 per CU
+    items, stats = plan_for(sh, P, C)
+    wide = items[items[:, F["wide"]] == 1]
+    assert stats["wide_items"] == 2048 and len(wide) == 2048 and (wide[:, F["pair_tok1"]] > 0).all()
+    first = wide[:, F["q_tok0"]] // 64
+    second = (wide[:, F["pair_tok1"]] - 1) // 64
+    assert ((first + second) == 63).all() and (wide[:, F["pair_ntok"]] == 64).all()
+    # every (sequence, KV head, tile) exactly once, as a first or as a second tile
+    key = lambda t: (wide[:, F["seq"]] * 8 + wide[:, F["kv_head"]]) * 64 + t
+    seen = np.concatenate([key(first), key(second)])
+    assert len(np.unique(seen)) == 4096 == len(seen)
+    # the keys of both tiles of an item add up to a constant
+    assert (wide[:, F["kv_end"]] + wide[:, F["pair_tok1"]] - 1 + 64 == 4096 + 64).all()
+    # an odd number of tiles leaves the middle one single; small cases go through the full check
+    check_plan(sh, [0] * 16, [64 * 33] * 16)
+    items, _ = plan_for(sh, [0] * 16, [64 * 33] * 16)
+    wide = items[items[:, F["wide"]] == 1]
+    assert (wide[:, F["pair_tok1"]] == 0).sum() == 16 * 8
+    # the benchmark batches keep single tiles (8 tiles per CU)
+    b = W.draw_batch(3)
+    items, _ = plan_for(b.shape, b.prefix_lens, b.chunk_lens)
+    assert (items[:, F["pair_tok1"]] == 0).all()
