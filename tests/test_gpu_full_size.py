@@ -53,7 +53,7 @@ def test_paper_shaped_iteration_long_context_every_row():
     U.assert_within_tolerance(rep)
 
 
-@pytest.mark.parametrize("kind", ["bf16", "fp8"])
+@pytest.mark.parametrize("kind", ["bf16", "fp8", "bf16_prefix"])
 def test_whole_prompts_paired_tiles_every_row(kind):
     """Whole prompts (prefix 0; the prefill that precedes the hand-over of section 4.2) with
     16 tiles per CU: the planner gives each work-group an early and a late tile of one
@@ -61,10 +61,14 @@ def test_whole_prompts_paired_tiles_every_row(kind):
     odd tile counts (a single middle tile); every output row is checked."""
     if kind == "bf16":
         shape, C = W.SHAPE_8B, [4096, 4100, 4031, 4160, 3900, 4200, 4097, 4223, 1500]
-    else:
+        P = [0] * len(C)
+    elif kind == "fp8":
         shape, C = W.SHAPE_70B, [4096, 4100, 4031, 4223, 720]
-    batch = W.custom_batch(shape, [0] * len(C), C, seed=4242)
-    it = DeviceIteration(batch, pool_fill=0x7FC1 if kind == "bf16" else 0x7F)
+        P = [0] * len(C)
+    else:  # long continuation chunks pair the same way: the second tile starts at key 0 of a non-empty prefix
+        shape, C, P = W.SHAPE_8B, [5500, 5440, 5503, 5567, 5500, 5570], [0, 64, 1000, 37, 500, 2049]
+    batch = W.custom_batch(shape, P, C, seed=4242)
+    it = DeviceIteration(batch, pool_fill=0x7F if kind == "fp8" else 0x7FC1)
     kv_bits = it.load_host_inputs()
     ks = vs = None
     if it.fp8:
