@@ -50,7 +50,34 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
   const int group = std::min(G, kNarrowRows);          // q heads handled together by one item
   const int n_groups = (G + group - 1) / group;        // > 1 only when G > 32
   const int wide_rows = wide_rows_for(D, cache->kv_dtype);
-  const int wide_tok = std::max(1, wide_rows / group);  // tokens per wide tile
+  // Tokens per wide tile.  A launch whose items would not even fill the CUs once and whose
+  // tiles are too short to be cut into key spans (one chunk of a few hundred tokens with
+  // little context next to a few decodes: the iteration of section 5.1 early in a request,
+  // or a short whole prompt) takes half tiles, 128 rows: four of the eight waves own rows,
+  // a tile's time drops by a quarter, and twice as many CUs work.
+  // (Measured on MI355X: a 512-token chunk behind 1024 cached tokens 40.6 -> 29.6 us; quarter
+  // tiles are slower again, and with the CUs already filled half tiles cost 1.5x the CU time.)
+  constexpr int kMinPiece = 16 * kWideKvTile;  // no key span of a wide tile is shorter
+  int wide_tok = std::max(1, wide_rows / group);
+  {
+    long long full_tiles = 0, narrow_items = 0;
+    double tile_keys = 0;
+    for (int s = 0; s < n_seqs; ++s) {
+      const long long P = prefix_lens[s], C = chunk_lens[s];
+      if (C <= 0 || P < 0) continue;
+      if (C * group <= kNarrowRows) { narrow_items += (long long)Hkv * n_groups; continue; }
+      const long long rem = C % wide_tok, full = C / wide_tok;
+      const bool wide_rem = rem && rem * group > kNarrowRows;
+      full_tiles += (full + wide_rem) * Hkv * n_groups;
+      narrow_items += (rem && !wide_rem) ? (long long)Hkv * n_groups : 0;
+      tile_keys += ((double)full * P + (double)wide_tok * full * (full + 1) / 2 + (wide_rem ? (double)(P + C) : 0.0)) *
+                   Hkv * n_groups;
+    }
+    const int cus = std::max(n_cus, 1);
+    if (full_tiles > 0 && 2 * full_tiles + narrow_items <= cus && tile_keys < (double)kMinPiece * cus &&
+        (wide_tok / 2) * group > kNarrowRows)
+      wide_tok /= 2;
+  }
 
   // keys read by narrow items, to size the spans, and the cost of the wide tiles in the
   // planner's unit (one key of a full wide tile = wide_rows / 128, one key of a narrow
@@ -88,7 +115,6 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
   if (wide_cost_total > 0) {
     const double fair = (wide_cost_total + 0.5 * narrow_keys) / std::max(n_cus, 1);
     const double keys = 0.75 * fair / (wide_rows / 128.0);
-    constexpr int kMinPiece = 16 * kWideKvTile;
     wide_piece_keys = (int)std::min<double>(std::max<double>(keys, kMinPiece), 1 << 30);
     wide_piece_keys = (wide_piece_keys + kWideKvTile - 1) / kWideKvTile * kWideKvTile;
   }

@@ -165,3 +165,22 @@ def test_many_tiles_per_cu_are_paired():
     b = W.draw_batch(3)
     items, _ = plan_for(b.shape, b.prefix_lens, b.chunk_lens)
     assert (items[:, F["pair_tok1"]] == 0).all()
+
+
+def test_small_launches_take_half_tiles():
+    """A launch that cannot fill the CUs once, with tiles too short for key spans, uses
+    tiles of 128 rows; with more decodes, more chunks or a long context it keeps 256."""
+    sh = W.SHAPE_8B
+    tok = lambda items: set(int(n) for n in items[items[:, F["wide"]] == 1][:, F["n_tok"]])
+    items, _ = check_plan(sh, [1024] + [999] * 8, [512] + [1] * 8)      # 2*64 + 64 items <= 256 CUs
+    assert tok(items) == {32}
+    items, _ = check_plan(sh, [0], [1010])                               # a short whole prompt, ragged end
+    assert tok(items) == {32, 18}
+    items, _ = check_plan(sh, [1024] + [999] * 32, [512] + [1] * 32)    # 2*64 + 256 items: CUs are busy anyway
+    assert tok(items) == {64}
+    items, _ = check_plan(sh, [1024] * 3, [512] * 3)                    # 192 full tiles
+    assert tok(items) == {64}
+    items, stats = check_plan(sh, [16384], [512])                        # long context: key spans instead
+    assert tok(items) == {64} and stats["partials"] > 0
+    items, _ = check_plan(W.HeadShape(64, 8, 128, "fp8"), [300], [200])  # G = 8: 16-token half tiles
+    assert tok(items) == {16, 8}
