@@ -60,8 +60,7 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
   constexpr int kMinPiece = 16 * kWideKvTile;  // no key span of a wide tile is shorter
   int wide_tok = std::max(1, wide_rows / group);
   {
-    long long full_tiles = 0, narrow_items = 0;
-    double tile_keys = 0;
+    long long full_tiles = 0, narrow_items = 0, longest = 0;
     for (int s = 0; s < n_seqs; ++s) {
       const long long P = prefix_lens[s], C = chunk_lens[s];
       if (C <= 0 || P < 0) continue;
@@ -70,11 +69,10 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
       const bool wide_rem = rem && rem * group > kNarrowRows;
       full_tiles += (full + wide_rem) * Hkv * n_groups;
       narrow_items += (rem && !wide_rem) ? (long long)Hkv * n_groups : 0;
-      tile_keys += ((double)full * P + (double)wide_tok * full * (full + 1) / 2 + (wide_rem ? (double)(P + C) : 0.0)) *
-                   Hkv * n_groups;
+      longest = std::max(longest, P + C);
     }
-    const int cus = std::max(n_cus, 1);
-    if (full_tiles > 0 && 2 * full_tiles + narrow_items <= cus && tile_keys < (double)kMinPiece * cus &&
+    // (a tile of more than 1.5 minimum spans is cut over its keys below, which serves such a launch better)
+    if (full_tiles > 0 && 2 * full_tiles + narrow_items <= std::max(n_cus, 1) && longest <= kMinPiece + kMinPiece / 2 &&
         (wide_tok / 2) * group > kNarrowRows)
       wide_tok /= 2;
   }

@@ -180,6 +180,8 @@ def test_small_launches_take_half_tiles():
     assert tok(items) == {64}
     items, _ = check_plan(sh, [1024] * 3, [512] * 3)                    # 192 full tiles
     assert tok(items) == {64}
+    items, stats = check_plan(sh, [2048], [512])                         # tiles long enough for two key spans
+    assert tok(items) == {64} and stats["partials"] > 0
     items, stats = check_plan(sh, [16384], [512])                        # long context: key spans instead
     assert tok(items) == {64} and stats["partials"] > 0
     items, _ = check_plan(W.HeadShape(64, 8, 128, "fp8"), [300], [200])  # G = 8: 16-token half tiles
