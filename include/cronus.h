@@ -118,8 +118,10 @@ int cronus_kv_append(const cronus_kv_cache* cache, const void* k_src, const void
  *   sm_scale     : softmax scale, normally 1/sqrt(D)
  *   workspace    : device, at least cronus_attn_mixed_workspace_bytes() bytes, 256-byte
  *                  aligned; holds the partial results of key spans until they are
- *                  merged; contents are undefined afterwards; must not be shared by
- *                  calls that can overlap on the device
+ *                  merged and, for an fp8 cache, a bf16 copy of the K/V of every sequence
+ *                  whose chunk spans 16 or more tiles (4 x Hkv x D bytes per cached or
+ *                  new token of such a sequence); contents are undefined afterwards;
+ *                  must not be shared by calls that can overlap on the device
  * The work list is built on the host during the call and read by the kernels from
  * pinned, device-mapped host memory that the library owns (a ring of 8 buffers, grown on
  * demand, never freed; the ninth call in flight waits on the host for the first).
@@ -149,7 +151,9 @@ int cronus_attn_mixed_plan_stats(const cronus_kv_cache* cache, const int32_t* pr
  * cronus_attn_mixed_plan_items - the work list itself, for inspection and tests (host
  * only, nothing is launched).  Writes up to `capacity` items, 12 int32 each, in grid
  * order: seq, kv_head, head0, n_heads, q_tok0, n_tok, kv_begin, kv_end, partial, wide,
- * pair_tok1, pair_ntok.  wide = 1: chunk tile over keys [kv_begin, kv_end); wide = 0:
+ * pair_tok1, pair_ntok.  wide >= 1: chunk tile over keys [kv_begin, kv_end) (wide >= 2,
+ * fp8 cache only: it reads the launch's bf16 copy of its sequence, whose first block
+ * there is wide - 2); wide = 0:
  * narrow item over keys [kv_begin, kv_end); partial >= 0 when the item's result is merged
  * with other spans of the same rows; wide = -1: idle slot.  pair_tok1 > 0 (wide items of
  * launches with many tiles per CU): the same work-group then also computes the earlier

@@ -11,6 +11,10 @@
 //                 gaps.  An item may name a second, earlier tile of the same sequence and
 //                 KV head, which the work-group computes afterwards (whole prompts with
 //                 many tiles per CU: half as many work-group starts).
+//                 For an fp8 cache a chunk of few tiles converts the codes on their way
+//                 into LDS (through registers, two stages); a chunk of many tiles reads a
+//                 bf16 copy of its sequence that kv_stage_kernel makes first, through the
+//                 same DMA pipeline as a bf16 cache.
 //   narrow item - at most 32 rows (a decode, or a short chunk) against a span of
 //                 keys; the 8 waves split the span and stream K/V chunks from the
 //                 paged pools through private LDS planes.
@@ -55,6 +59,10 @@ struct AttnParams {
   const WorkItem* items;
   const MergeItem* merges;
   float* partials;
+  const StageSeq* stage_seqs;   // fp8 cache: sequences with a bf16 copy of their K/V in the workspace
+  unsigned char* stage_k;       // the copy: [block][Hkv][16 x D bf16], chunk layout as in the cache
+  unsigned char* stage_v;
+  int n_stage_seqs;
   int max_blocks;
   int n_q_heads;
   int n_kv_heads;
@@ -479,7 +487,10 @@ __device__ __forceinline__ void static_for(F&& f) {
 // fetching 1/8 of a tile; one s_barrier per tile publishes a landed tile and frees the
 // stage of the tile before last.  Between barriers the 8 waves run freely, so the two
 // waves of a SIMD fill each other's VALU and MFMA gaps.
-template <int D>
+// COPY: the item's sequence belongs to an fp8 cache and its K/V is read from the bf16 copy
+// that kv_stage_kernel made for this launch (blocks it.wide - 2 .. in logical order, no
+// table); the scale of K enters the exponent constant, that of V the normalisation.
+template <int D, bool COPY>
 __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem& it, unsigned char* smem) {
   constexpr int NSTEP = D / 16, NDB = D / 32;
   constexpr int BLK_LDS = 16 * D * 2;     // bytes of one (block, head)
@@ -501,7 +512,13 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
   // key positions are counted from the item's first key (a multiple of the tile size)
   const int kv_len = si.prefix_len + si.chunk_len - it.kv_begin;
   const int pos0 = si.prefix_len + it.q_tok0 - it.kv_begin;
-  const float c = p.scale_log2e;
+  float c = p.scale_log2e, vmul = 1.0f;
+  if constexpr (COPY) {
+    c *= p.k_scale[it.kv_head];
+    vmul = p.v_scale[it.kv_head];
+  }
+  const unsigned char* const k_src = COPY ? p.stage_k : p.k_pool;
+  const unsigned char* const v_src = COPY ? p.stage_v : p.v_pool;
   const int wave_min_limit = pos0 + min(row_base, rows_valid - 1) / gi_n;
   const int wave_max_limit = wave_has_rows ? pos0 + min(row_base + 31, rows_valid - 1) / gi_n : -1;
 
@@ -526,6 +543,7 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
 
   const int blk0 = it.kv_begin >> 4;
   const int* bt = p.block_tables + (long long)it.seq * p.max_blocks + blk0;
+  const int copy_blk0 = it.wide - 2 + blk0;  // COPY: the copy's block of the span's first key
   const long long head_stride = (long long)BLK_LDS;
   const int n_sub = (it.kv_end - it.kv_begin + 31) >> 5;
   const int last_blk = si.n_blocks - 1 - blk0;
@@ -537,7 +555,8 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
   int bt_reg = 0;  // lane i: physical block of this wave's share of tile (64*k + i)
   auto issue_tile = [&](int j) {
     if ((j & 63) == 0) {
-      bt_reg = bt[min(4 * (j + lane) + blk_w, last_blk)];
+      if constexpr (COPY) bt_reg = copy_blk0 + min(4 * (j + lane) + blk_w, last_blk);
+      else bt_reg = bt[min(4 * (j + lane) + blk_w, last_blk)];
       asm volatile("" : "+v"(bt_reg));
     }
     const long long b = __builtin_amdgcn_readlane(bt_reg, j & 63);
@@ -545,23 +564,24 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
     lds_byte* dst = lds0 + (j % kStages) * STAGE + blk_w * BLK_LDS + part_w * 1024;
 #pragma unroll
     for (int x = 0; x < UPW; ++x) {
-      dma_1k(p.k_pool + goff + x * 1024, dst + x * 1024, lane);
-      dma_1k(p.v_pool + goff + x * 1024, dst + KT_BYTES + x * 1024, lane);
+      dma_1k(k_src + goff + x * 1024, dst + x * 1024, lane);
+      dma_1k(v_src + goff + x * 1024, dst + KT_BYTES + x * 1024, lane);
     }
   };
   // one of the NI instructions of tile j (q = 2 x + is_v), for spreading a tile's fetch
   // over the two sub-tile steps of a period
   auto issue_part = [&](int j, int q) {
     if (q == 0 && (j & 63) == 0) {
-      bt_reg = bt[min(4 * (j + lane) + blk_w, last_blk)];
+      if constexpr (COPY) bt_reg = copy_blk0 + min(4 * (j + lane) + blk_w, last_blk);
+      else bt_reg = bt[min(4 * (j + lane) + blk_w, last_blk)];
       asm volatile("" : "+v"(bt_reg));
     }
     const long long b = __builtin_amdgcn_readlane(bt_reg, j & 63);
     const long long goff = (b * p.n_kv_heads + it.kv_head) * head_stride + part_w * 1024;
     lds_byte* dst = lds0 + (j % kStages) * STAGE + blk_w * BLK_LDS + part_w * 1024;
     const int x = q >> 1;
-    if (q & 1) dma_1k(p.v_pool + goff + x * 1024, dst + KT_BYTES + x * 1024, lane);
-    else dma_1k(p.k_pool + goff + x * 1024, dst + x * 1024, lane);
+    if (q & 1) dma_1k(v_src + goff + x * 1024, dst + KT_BYTES + x * 1024, lane);
+    else dma_1k(k_src + goff + x * 1024, dst + x * 1024, lane);
   };
 
   // ---- LDS operand reads (byte addresses)
@@ -734,7 +754,7 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
       store_partial_row<NDB, D>(ps, c32, o, m * c, lt, half);
     } else {
       unsigned short* op = p.out + ((long long)(si.q_off + it.q_tok0 + t_row) * p.n_q_heads + it.head0 + gi_row) * D;
-      store_row_bf16<NDB>(op, o, 1.0f / lt, half);
+      store_row_bf16<NDB>(op, o, vmul / lt, half);
     }
   }
 }
@@ -994,8 +1014,12 @@ __global__ __launch_bounds__(kThreads) void attn_mixed_kernel(AttnParams p) {
     // the tile itself, then the earlier tile paired with it (if any): keys from 0, final output
     WorkItem cur = it;
     for (int rep = 0;; ++rep) {
-      if constexpr (FP8) run_wide_staged<D, FP8, 1>(p, cur, smem);
-      else run_wide_dma<D>(p, cur, smem);
+      if constexpr (FP8) {
+        if (cur.wide >= 2) run_wide_dma<D, true>(p, cur, smem);
+        else run_wide_staged<D, FP8, 1>(p, cur, smem);
+      } else {
+        run_wide_dma<D, false>(p, cur, smem);
+      }
       if (rep || it.pair_tok1 <= 0) break;
       cur.q_tok0 = it.pair_tok1 - 1;
       cur.n_tok = it.pair_ntok;
@@ -1006,6 +1030,39 @@ __global__ __launch_bounds__(kThreads) void attn_mixed_kernel(AttnParams p) {
     }
   } else {
     run_narrow<D, FP8>(p, it, smem);
+  }
+}
+
+// fp8 cache: bf16 copy of the K/V blocks of the sequences listed in p.stage_seqs (exact:
+// every e4m3 value is a bf16 value), one work-group per block of the copy, all KV heads.
+constexpr int kStageThreads = 256;
+template <int D>
+__global__ __launch_bounds__(kStageThreads) void kv_stage_kernel(AttnParams p) {
+  const int b = blockIdx.x;
+  // the entry that holds block b: entries are sorted by blk0; lanes test 64 of them at a time
+  const int lane = threadIdx.x & 63;
+  int e = 0;
+  for (int base = 0; base < p.n_stage_seqs; base += 64) {
+    const int i = base + lane;
+    const bool le = i < p.n_stage_seqs && p.stage_seqs[i].blk0 <= b;
+    const int n = __builtin_popcountll(__builtin_amdgcn_ballot_w64(le));
+    if (n == 0) break;
+    e = base + n - 1;
+    if (n < 64) break;
+  }
+  const StageSeq sq = p.stage_seqs[e];
+  const int j = b - sq.blk0;
+  if (j < 0 || j >= sq.n_blocks) return;
+  const long long phys = p.block_tables[(long long)sq.seq * p.max_blocks + j];
+  constexpr int SRC = 16 * D, DST = 32 * D;  // bytes of one (block, head): codes, bf16
+  for (int h = 0; h < p.n_kv_heads; ++h) {
+    const long long so = (phys * p.n_kv_heads + h) * SRC, dn = ((long long)b * p.n_kv_heads + h) * DST;
+    for (int ch = threadIdx.x; ch < SRC / 8; ch += kStageThreads) {
+      const u32x2 kc = *reinterpret_cast<const u32x2*>(p.k_pool + so + ch * 8);
+      const u32x2 vc = *reinterpret_cast<const u32x2*>(p.v_pool + so + ch * 8);
+      *reinterpret_cast<u32x4*>(p.stage_k + dn + ch * 16) = fp8x8_to_bf16x8(kc);
+      *reinterpret_cast<u32x4*>(p.stage_v + dn + ch * 16) = fp8x8_to_bf16x8(vc);
+    }
   }
 }
 
@@ -1046,12 +1103,18 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(AttnParams p)
 
 template <int D, bool FP8>
 int launch_typed(const AttnLaunch& a, const AttnParams& p) {
-  constexpr int wide_lds = (FP8 ? 2 : 4) * 2 * 4 * 16 * D * 2;  // stages x (K + V tile of 64 keys)
+  constexpr int wide_lds = 4 * 2 * 4 * 16 * D * 2;  // stages x (K + V tile of 64 keys)
   constexpr int narrow_lds = kWaves * (2 * (D / 16) * 1024) + kWaves * 2 * 64 * 4;
   constexpr int lds = wide_lds > narrow_lds ? wide_lds : narrow_lds;
   static_assert(lds <= 160 * 1024, "LDS budget");
   hipStream_t s = static_cast<hipStream_t>(a.stream);
   const Plan& pl = *a.plan;
+  if constexpr (FP8) {
+    if (pl.n_stage_blocks > 0) {
+      hipLaunchKernelGGL((kv_stage_kernel<D>), dim3((unsigned)pl.n_stage_blocks), dim3(kStageThreads), 0, s, p);
+      if (hipGetLastError() != hipSuccess) return CRONUS_ERR_HIP;
+    }
+  }
   if (pl.n_items > 0) {
     auto kern = attn_mixed_kernel<D, FP8>;
     static bool attr_set = false;
@@ -1098,6 +1161,10 @@ int launch_attn(const AttnLaunch& a) {
   p.items = reinterpret_cast<const WorkItem*>(image + pl.off_items);
   p.merges = reinterpret_cast<const MergeItem*>(image + pl.off_merge);
   p.partials = reinterpret_cast<float*>(ws + pl.off_partials);
+  p.stage_seqs = reinterpret_cast<const StageSeq*>(image + pl.off_stage);
+  p.stage_k = ws + pl.off_stage_k;
+  p.stage_v = ws + pl.off_stage_v;
+  p.n_stage_seqs = pl.n_stage_seqs;
   p.max_blocks = a.max_blocks_per_seq;
   p.n_q_heads = c.num_q_heads;
   p.n_kv_heads = c.num_kv_heads;

@@ -35,7 +35,9 @@ struct WorkItem {
   int32_t kv_begin;  // keys [kv_begin, kv_end) are processed by this item
   int32_t kv_end;
   int32_t partial;   // < 0: writes final output; else index of its (wide: first of kWaves) partial-result slot(s)
-  int32_t wide;      // 1: chunk tile staged through LDS; 0: narrow (<= 32 rows), waves split keys; -1: idle slot
+  int32_t wide;      // 1: chunk tile staged through LDS; >= 2: the same, reading the bf16 copy of an fp8
+                     // sequence's K/V whose first block in the copy is wide - 2; 0: narrow (<= 32 rows),
+                     // waves split keys; -1: idle slot
   // copy of the sequence's record, so that a work-group needs one dependent load less
   // before it can address Q and the block table
   int32_t prefix_len, chunk_len, q_off, n_blocks;
@@ -67,13 +69,25 @@ struct MergeItem {
   int32_t q_off;  // the sequence's first row in q/out (copy of SeqInfo::q_off: one dependent load less)
 };
 
+// A sequence of an fp8 cache whose chunk has many tiles: its K/V blocks 0 .. n_blocks - 1 are
+// converted to bf16 once per launch, into blocks blk0 .. of a copy in the workspace (same
+// layout as the cache, 2 bytes per element), and its wide tiles read that copy.
+struct StageSeq {
+  int32_t seq;
+  int32_t blk0;
+  int32_t n_blocks;
+  int32_t pad;
+};
+
 struct Plan {
   // sizes
   int64_t n_items = 0, n_wide = 0, n_partials = 0, n_merge = 0, n_merge_rows = 0;
   int32_t n_seqs = 0;
   int32_t wide_rows = 0;  // rows per wide tile (compile-time choice of the kernel instance)
+  int32_t n_stage_seqs = 0;
+  int64_t n_stage_blocks = 0;
   // byte offsets inside the workspace
-  size_t off_items = 0, off_merge = 0, off_partials = 0, total_bytes = 0;
+  size_t off_items = 0, off_merge = 0, off_stage = 0, off_partials = 0, off_stage_k = 0, off_stage_v = 0, total_bytes = 0;
   size_t upload_bytes = 0;  // [0, upload_bytes) is host-built metadata
 };
 

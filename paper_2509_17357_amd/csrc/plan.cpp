@@ -32,6 +32,7 @@ struct Scratch {
   std::vector<float> wide_cost;
   std::vector<Group> groups;
   std::vector<MergeItem> merges;
+  std::vector<StageSeq> stages;
   std::vector<int32_t> queue[kXcds];  // item references: >= 0 wide index, < 0 ~narrow index
   std::vector<int32_t> order, bucket_start;
 };
@@ -129,7 +130,13 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
   sc.wide_cost.clear();
   sc.groups.clear();
   sc.merges.clear();
-  int64_t n_partials = 0, n_merge_rows = 0;
+  sc.stages.clear();
+  int64_t n_partials = 0, n_merge_rows = 0, n_stage_blocks = 0;
+  // fp8 cache: a chunk of many tiles reads each key of its sequence that many times; its
+  // K/V is then converted to bf16 once (into the workspace) and the tiles run on the bf16
+  // pipeline (measured on the chunks of the 70B-shaped batch: 7.66 -> 6.6 ms of attention).
+  constexpr int kStageMinTiles = 16;
+  const bool fp8 = cache->kv_dtype == CRONUS_KV_FP8_E4M3;
   int32_t q_off = 0;
 
   auto add_narrow = [&](int s, int kvh, int head0, int nh, int q_tok0, int n_tok, int kv_total) {
@@ -166,6 +173,16 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
           continue;
         }
         Group g{(int32_t)sc.wide.size(), 0, 0.f};
+        int32_t wide_tag = 1;
+        if (fp8 && (C + wide_tok - 1) / wide_tok >= kStageMinTiles) {
+          if (sc.stages.empty() || sc.stages.back().seq != s) {
+            const int32_t nb = (P + C + kBlock - 1) / kBlock;
+            if (n_stage_blocks + nb > 0x7ffffff0LL) return CRONUS_ERR_INVALID_ARG;
+            sc.stages.push_back(StageSeq{s, (int32_t)n_stage_blocks, nb, 0});
+            n_stage_blocks += nb;
+          }
+          wide_tag = 2 + sc.stages.back().blk0;
+        }
         for (int t0 = 0; t0 < C; t0 += wide_tok) {
           const int nt = std::min(wide_tok, C - t0);
           if (nt * group <= kNarrowRows) {
@@ -200,7 +217,7 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
               w.partial = (int32_t)n_partials;
               n_partials += kWaves;
             }
-            w.wide = 1;
+            w.wide = wide_tag;
             const float cost = (float)(w.kv_end - w.kv_begin) * cost_per_key;
             sc.wide.push_back(w);
             sc.wide_cost.push_back(cost);
@@ -350,9 +367,15 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
   plan->n_merge_rows = n_merge_rows;
   plan->off_items = 0;
   plan->off_merge = align_up(plan->off_items + sizeof(WorkItem) * n_slots, 256);
-  plan->upload_bytes = align_up(plan->off_merge + sizeof(MergeItem) * sc.merges.size(), 256);
+  plan->n_stage_seqs = (int32_t)sc.stages.size();
+  plan->n_stage_blocks = n_stage_blocks;
+  plan->off_stage = align_up(plan->off_merge + sizeof(MergeItem) * sc.merges.size(), 256);
+  plan->upload_bytes = align_up(plan->off_stage + sizeof(StageSeq) * sc.stages.size(), 256);
   plan->off_partials = plan->upload_bytes;
-  plan->total_bytes = align_up(plan->off_partials + sizeof(float) * partial_floats(D) * (size_t)n_partials, 256);
+  plan->off_stage_k = align_up(plan->off_partials + sizeof(float) * partial_floats(D) * (size_t)n_partials, 256);
+  const size_t stage_bytes = (size_t)n_stage_blocks * Hkv * kBlock * D * 2;  // bf16 copy of K (and of V)
+  plan->off_stage_v = align_up(plan->off_stage_k + stage_bytes, 256);
+  plan->total_bytes = align_up(plan->off_stage_v + stage_bytes, 256);
   if (plan->total_bytes == 0) plan->total_bytes = 256;
 
   return CRONUS_OK;
@@ -387,6 +410,7 @@ void write_plan(const Plan* plan, void* host_buf) {
     for (MergeItem& mi : sc.merges) mi.q_off = sc.seqs[(size_t)mi.seq].q_off;
     std::memcpy(h + plan->off_merge, sc.merges.data(), sizeof(MergeItem) * sc.merges.size());
   }
+  if (!sc.stages.empty()) std::memcpy(h + plan->off_stage, sc.stages.data(), sizeof(StageSeq) * sc.stages.size());
 }
 
 }  // namespace cronus

@@ -79,7 +79,7 @@ def test_whole_prompts_paired_tiles_every_row(kind):
     torch.cuda.synchronize()
     items = B.cronus_attn_mixed_plan_items(it.cache, batch.prefix_lens, batch.chunk_lens)
     F = {n: i for i, n in enumerate(B.PLAN_ITEM_FIELDS)}
-    wide = items[items[:, F["wide"]] == 1]
+    wide = items[items[:, F["wide"]] >= 1]
     assert (wide[:, F["pair_tok1"]] > 0).sum() > 0.9 * len(wide)      # the paired path is what runs
     assert (wide[:, F["pair_tok1"]] == 0).sum() > 0                    # and some single middle tiles
     ref = U.oracle_attention(batch, bits_from_bf16_tensor(it.q), U.oracle_kv_values(batch, kv_bits, ks, vs),

@@ -26,7 +26,7 @@ def check_plan(shape, P, C):
     G = shape.n_q_heads // shape.n_kv_heads
     real = items[items[:, F["wide"]] >= 0]
     assert (items[items[:, F["wide"]] < 0][:, :8] == 0).all()  # idle slots carry nothing
-    assert (real[:, F["wide"]] == 1).sum() == stats["wide_items"]
+    assert (real[:, F["wide"]] >= 1).sum() == stats["wide_items"]
     # coverage[s][head, token] = list of (kv_begin, kv_end, partial)
     cover = {}
     tiles = []
@@ -68,7 +68,7 @@ def check_plan(shape, P, C):
     # each partial slot belongs to one item: a narrow item owns one, a split wide tile one per wavefront
     slots = []
     for it in real[real[:, F["partial"]] >= 0]:
-        slots += list(range(int(it[F["partial"]]), int(it[F["partial"]]) + (8 if it[F["wide"]] == 1 else 1)))
+        slots += list(range(int(it[F["partial"]]), int(it[F["partial"]]) + (8 if it[F["wide"]] >= 1 else 1)))
     assert sorted(slots) == list(range(stats["partials"]))
     return items, stats
 
@@ -97,7 +97,7 @@ def test_plan_queues_follow_xcd_order():
     queues, and within a queue they come longest first."""
     b = W.draw_batch(3)
     items, _ = plan_for(b.shape, b.prefix_lens, b.chunk_lens)
-    wide = [(i % 8, it) for i, it in enumerate(items) if it[F["wide"]] == 1]
+    wide = [(i % 8, it) for i, it in enumerate(items) if it[F["wide"]] >= 1]
     queues_of = {}
     for x, it in wide:
         queues_of.setdefault((int(it[F["seq"]]), int(it[F["kv_head"]])), set()).add(x)
@@ -114,7 +114,7 @@ def test_plan_queues_follow_xcd_order():
     # the eight queues carry similar amounts of work
     load = np.zeros(8)
     for i, it in enumerate(items):
-        if it[F["wide"]] == 1:
+        if it[F["wide"]] >= 1:
             load[i % 8] += 2.0 * (it[F["kv_end"]] - it[F["kv_begin"]])
         elif it[F["wide"]] == 0:
             load[i % 8] += 0.5 * (it[F["kv_end"]] - it[F["kv_begin"]])
@@ -127,14 +127,14 @@ def test_few_long_wide_tiles_are_split_over_keys():
     while a batch with many tiles per CU is left alone."""
     sh = W.SHAPE_8B
     items, stats = check_plan(sh, [32768] + [999] * 16, [496] + [1] * 16)
-    wide = items[items[:, F["wide"]] == 1]
+    wide = items[items[:, F["wide"]] >= 1]
     tiles = {(int(i[F["kv_head"]]), int(i[F["q_tok0"]])) for i in wide}
     assert len(tiles) == 8 * 8 and len(wide) >= 4 * len(tiles)
     span = wide[:, F["kv_end"]] - wide[:, F["kv_begin"]]
     assert span.max() <= 2 * span[span > 256].min() + 64   # spans of one size, up to the tail
     b = W.draw_batch(3)
     items3, _ = plan_for(b.shape, b.prefix_lens, b.chunk_lens)
-    w3 = items3[items3[:, F["wide"]] == 1]
+    w3 = items3[items3[:, F["wide"]] >= 1]
     assert (w3[:, F["kv_begin"]] == 0).all() and (w3[:, F["partial"]] == -1).all()
 
 
@@ -145,7 +145,7 @@ def test_many_tiles_per_cu_are_paired():
     sh = W.HeadShape(32, 8, 128)
     P, C = [0] * 8, [4096] * 8                      # 8 x 64 tiles x 8 KV heads = 4096 tiles, 16 per CU
     items, stats = plan_for(sh, P, C)
-    wide = items[items[:, F["wide"]] == 1]
+    wide = items[items[:, F["wide"]] >= 1]
     assert stats["wide_items"] == 2048 and len(wide) == 2048 and (wide[:, F["pair_tok1"]] > 0).all()
     first = wide[:, F["q_tok0"]] // 64
     second = (wide[:, F["pair_tok1"]] - 1) // 64
@@ -159,7 +159,7 @@ def test_many_tiles_per_cu_are_paired():
     # an odd number of tiles leaves the middle one single; small cases go through the full check
     check_plan(sh, [0] * 16, [64 * 33] * 16)
     items, _ = plan_for(sh, [0] * 16, [64 * 33] * 16)
-    wide = items[items[:, F["wide"]] == 1]
+    wide = items[items[:, F["wide"]] >= 1]
     assert (wide[:, F["pair_tok1"]] == 0).sum() == 16 * 8
     # the benchmark batches keep single tiles (8 tiles per CU)
     b = W.draw_batch(3)
@@ -171,7 +171,7 @@ def test_small_launches_take_half_tiles():
     """A launch that cannot fill the CUs once, with tiles too short for key spans, uses
     tiles of 128 rows; with more decodes, more chunks or a long context it keeps 256."""
     sh = W.SHAPE_8B
-    tok = lambda items: set(int(n) for n in items[items[:, F["wide"]] == 1][:, F["n_tok"]])
+    tok = lambda items: set(int(n) for n in items[items[:, F["wide"]] >= 1][:, F["n_tok"]])
     items, _ = check_plan(sh, [1024] + [999] * 8, [512] + [1] * 8)      # 2*64 + 64 items <= 256 CUs
     assert tok(items) == {32}
     items, _ = check_plan(sh, [0], [1010])                               # a short whole prompt, ragged end
@@ -186,3 +186,29 @@ def test_small_launches_take_half_tiles():
     assert tok(items) == {64} and stats["partials"] > 0
     items, _ = check_plan(W.HeadShape(64, 8, 128, "fp8"), [300], [200])  # G = 8: 16-token half tiles
     assert tok(items) == {16, 8}
+
+
+def test_fp8_chunks_of_many_tiles_read_a_bf16_copy():
+    """fp8 cache: a sequence whose chunk has 16 or more tiles gets blocks in the launch's bf16
+    copy (wide = 2 + its first block there, blocks dealt in batch order); shorter chunks,
+    decodes and bf16 caches do not; the workspace grows by the copy."""
+    sh = W.HeadShape(64, 8, 128, "fp8")                      # G = 8: 32 tokens per tile
+    P, C = [1000, 0, 5000, 77, 40], [600, 100, 513, 1, 2048]
+    items, stats = check_plan(sh, P, C)
+    wide = items[items[:, F["wide"]] >= 1]
+    by_seq = {s: set(int(w) for w in wide[wide[:, F["seq"]] == s][:, F["wide"]]) for s in range(5)}
+    blocks = lambda s: (P[s] + C[s] + 15) // 16
+    assert by_seq[0] == {2}                                   # 19 tiles: first in the copy
+    assert by_seq[1] == {1}                                   # 4 tiles: staged through registers
+    assert by_seq[2] == {2 + blocks(0)}                       # 17 tiles (the last one partial)
+    assert by_seq[3] == set()                                 # a decode
+    assert by_seq[4] == {2 + blocks(0) + blocks(2)}
+    c = B.make_cache(0, 0, 1 << 20, 64, 8, 128, B.CRONUS_KV_FP8_E4M3)
+    need = B.cronus_attn_mixed_workspace_bytes(c, P, C)
+    copy_bytes = 2 * (blocks(0) + blocks(2) + blocks(4)) * 8 * 16 * 128 * 2
+    assert need >= copy_bytes and need < copy_bytes + (64 << 20)
+    # the same lengths on a bf16 cache: nothing is copied
+    items, _ = check_plan(W.HeadShape(64, 8, 128), P, C)
+    assert set(int(w) for w in items[:, F["wide"]]) <= {-1, 0, 1}
+    cb = B.make_cache(0, 0, 1 << 20, 64, 8, 128)
+    assert B.cronus_attn_mixed_workspace_bytes(cb, P, C) < copy_bytes
