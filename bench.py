@@ -39,8 +39,8 @@ BOUND = {"tiny": "hbm", "llama3_8b": "hbm", "prefill_heavy": "mfma", "decode_hea
 # HBM bytes per attention-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled
 # by what the same counters read for a plain 1 GiB copy (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000):
 # profiles/attn_mixed_kernel_benchmark_batches_rocprofv3.md.  None where not measured.
-MEASURED_TRAFFIC_BYTES = {"tiny": None, "llama3_8b": 624380551, "prefill_heavy": 567759032,
-                          "decode_heavy": 4868595995, "llama_70b_fp8": 3484317472}
+MEASURED_TRAFFIC_BYTES = {"tiny": None, "llama3_8b": 624460157, "prefill_heavy": 568301344,
+                          "decode_heavy": 4868596580, "llama_70b_fp8": 3998651460}
 
 
 def time_workload(name, steps, warmup, trial=0):
