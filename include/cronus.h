@@ -120,7 +120,8 @@ int cronus_kv_append(const cronus_kv_cache* cache, const void* k_src, const void
  *                  aligned; holds the partial results of key spans until they are
  *                  merged and, for an fp8 cache, a bf16 copy of the K/V of every sequence
  *                  whose chunk spans 16 or more tiles (4 x Hkv x D bytes per cached or
- *                  new token of such a sequence); contents are undefined afterwards;
+ *                  new token of such a sequence, 1 GiB at most: sequences beyond that
+ *                  are computed from the codes); contents are undefined afterwards;
  *                  must not be shared by calls that can overlap on the device
  * The work list is built on the host during the call and read by the kernels from
  * pinned, device-mapped host memory that the library owns (a ring of 8 buffers, grown on

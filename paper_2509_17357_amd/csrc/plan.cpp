@@ -136,6 +136,8 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
   // K/V is then converted to bf16 once (into the workspace) and the tiles run on the bf16
   // pipeline (measured on the chunks of the 70B-shaped batch: 7.66 -> 6.6 ms of attention).
   constexpr int kStageMinTiles = 16;
+  constexpr long long kStageMaxBytes = 1LL << 30;  // of workspace for the copy; later sequences convert on the fly
+  const long long stage_block_bytes = 2LL * Hkv * kBlock * D * 2;  // K and V of one block, bf16
   const bool fp8 = cache->kv_dtype == CRONUS_KV_FP8_E4M3;
   int32_t q_off = 0;
 
@@ -175,13 +177,13 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
         Group g{(int32_t)sc.wide.size(), 0, 0.f};
         int32_t wide_tag = 1;
         if (fp8 && (C + wide_tok - 1) / wide_tok >= kStageMinTiles) {
-          if (sc.stages.empty() || sc.stages.back().seq != s) {
-            const int32_t nb = (P + C + kBlock - 1) / kBlock;
-            if (n_stage_blocks + nb > 0x7ffffff0LL) return CRONUS_ERR_INVALID_ARG;
+          const int32_t nb = (P + C + kBlock - 1) / kBlock;
+          const bool listed = !sc.stages.empty() && sc.stages.back().seq == s;
+          if (!listed && (n_stage_blocks + nb) * stage_block_bytes <= kStageMaxBytes) {
             sc.stages.push_back(StageSeq{s, (int32_t)n_stage_blocks, nb, 0});
             n_stage_blocks += nb;
           }
-          wide_tag = 2 + sc.stages.back().blk0;
+          if (!sc.stages.empty() && sc.stages.back().seq == s) wide_tag = 2 + sc.stages.back().blk0;
         }
         for (int t0 = 0; t0 < C; t0 += wide_tok) {
           const int nt = std::min(wide_tok, C - t0);

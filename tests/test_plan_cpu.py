@@ -212,3 +212,10 @@ def test_fp8_chunks_of_many_tiles_read_a_bf16_copy():
     assert set(int(w) for w in items[:, F["wide"]]) <= {-1, 0, 1}
     cb = B.make_cache(0, 0, 1 << 20, 64, 8, 128)
     assert B.cronus_attn_mixed_workspace_bytes(cb, P, C) < copy_bytes
+    # the copy is bounded (1 GiB of workspace): sequences past the bound convert on the fly
+    P, C = [200000, 200000, 100], [1024, 1024, 1024]
+    items, _ = plan_for(sh, P, C)
+    wide = items[items[:, F["wide"]] >= 1]
+    tags = [set(int(w) for w in wide[wide[:, F["seq"]] == s][:, F["wide"]]) for s in range(3)]
+    assert tags[0] == {2} and tags[1] == {1} and tags[2] == {2 + (200000 + 1024 + 15) // 16}
+    assert B.cronus_attn_mixed_workspace_bytes(c, P, C) < (1 << 30) + (256 << 20)
