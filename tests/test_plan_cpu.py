@@ -35,8 +35,8 @@ def check_plan(shape, P, C):
         tiles.append((s, kvh, h0, nh, t0, nt, kb, ke, part, wide))
         if pair1:
             # the second tile of a work-group: earlier tokens of the same heads, whole, final
-            assert wide == 1 and part == -1 and kb == 0 and 0 <= pair1 - 1 < t0 and pair_nt * nh > 32
-            tiles.append((s, kvh, h0, nh, pair1 - 1, pair_nt, 0, int(P[s]) + pair1 - 1 + pair_nt, -1, 1))
+            assert wide >= 1 and part == -1 and kb == 0 and 0 <= pair1 - 1 < t0 and pair_nt * nh > 32
+            tiles.append((s, kvh, h0, nh, pair1 - 1, pair_nt, 0, int(P[s]) + pair1 - 1 + pair_nt, -1, wide))
         else:
             assert pair_nt == 0
     for s, kvh, h0, nh, t0, nt, kb, ke, part, wide in tiles:
@@ -219,3 +219,22 @@ def test_fp8_chunks_of_many_tiles_read_a_bf16_copy():
     tags = [set(int(w) for w in wide[wide[:, F["seq"]] == s][:, F["wide"]]) for s in range(3)]
     assert tags[0] == {2} and tags[1] == {1} and tags[2] == {2 + (200000 + 1024 + 15) // 16}
     assert B.cronus_attn_mixed_workspace_bytes(c, P, C) < (1 << 30) + (256 << 20)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_plan_random_batches_cover_every_row_once(seed):
+    """Seeded random batches over head shapes, cache types and length mixes (empty sequences,
+    decodes, short and long chunks, long prefixes): the coverage and alignment invariants of
+    check_plan hold whatever mix of tile sizes, key spans, pairs and copies the planner picks."""
+    rng = np.random.default_rng([seed, 0x91A])
+    shape = [W.HeadShape(32, 8, 128), W.HeadShape(28, 4, 128), W.HeadShape(8, 2, 64), W.HeadShape(64, 8, 128, "fp8"),
+             W.HeadShape(16, 16, 64), W.HeadShape(64, 1, 128), W.HeadShape(16, 2, 128, "fp8")][seed % 7]
+    n = int(rng.integers(1, 12))
+    kind = rng.integers(0, 4, n)                   # empty, decode, short chunk, long chunk
+    C = np.where(kind == 0, 0, np.where(kind == 1, 1, np.where(kind == 2, rng.integers(2, 70, n), rng.integers(70, 900, n))))
+    P = np.where(rng.random(n) < 0.3, 0, rng.integers(0, 6000, n))
+    if seed % 3 == 0:                              # one long context
+        P[int(rng.integers(0, n))] = int(rng.integers(20000, 40000))
+    if C.sum() == 0:
+        C[0] = 1
+    check_plan(shape, P.astype(np.int64), C.astype(np.int64))
