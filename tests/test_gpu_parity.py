@@ -171,6 +171,28 @@ def test_config2_scaled_down():
     U.assert_within_tolerance(run_batch(W.draw_batch(2, scale=0.25)))
 
 
+def test_fp8_chunks_of_many_tiles_over_the_bf16_copy():
+    """fp8 cache, chunks of 16 or more tiles: their sequences are converted to bf16 once and
+    the tiles read that copy.  One chunk sits behind a long prefix (its tiles are cut into key
+    spans and merged: partial results carry the K scale in their exponents, the merge applies
+    the V scale), one behind a short prefix with a ragged last tile, one chunk is too short
+    for the copy and converts on the fly, and decodes read codes."""
+    shape = W.HeadShape(16, 2, 128, "fp8")                       # G = 8: 32 tokens per tile
+    P, C = [20000, 300, 77, 9000, 4000], [600, 530, 100, 1, 1]
+    batch = W.custom_batch(shape, P, C, seed=4420)
+    from paper_2509_17357_amd import binding as B
+    c = B.make_cache(0, 0, 1 << 20, 16, 2, 128, B.CRONUS_KV_FP8_E4M3)
+    items = B.cronus_attn_mixed_plan_items(c, P, C)
+    F = {n: i for i, n in enumerate(B.PLAN_ITEM_FIELDS)}
+    copy = items[items[:, F["wide"]] >= 2]
+    assert set(int(x) for x in copy[:, F["seq"]]) == {0, 1} and (copy[:, F["partial"]] >= 0).any()
+    real = items[items[:, F["wide"]] >= 0]
+    assert set(int(x) for x in real[real[:, F["seq"]] == 2][:, F["wide"]]) == {0, 1}   # three tiles and a narrow tail
+    U.assert_within_tolerance(run_batch(batch))
+    # D = 64 and MQA: other strides in the copy
+    U.assert_within_tolerance(run_batch(W.custom_batch(W.HeadShape(8, 1, 64, "fp8"), [5000, 0], [640, 520], seed=4421)))
+
+
 def test_fp8_cache_head_dim_64():
     batch = W.custom_batch(W.HeadShape(8, 2, 64, "fp8"), [300, 20, 1500], [140, 1, 1], seed=4410)
     U.assert_within_tolerance(run_batch(batch))
