@@ -119,7 +119,8 @@ int cronus_kv_append(const cronus_kv_cache* cache, const void* k_src, const void
  *   workspace    : device, at least cronus_attn_mixed_workspace_bytes() bytes, 256-byte
  *                  aligned; holds the partial results of key spans until they are
  *                  merged and, for an fp8 cache, a bf16 copy of the K/V of every sequence
- *                  whose chunk spans 16 or more tiles (4 x Hkv x D bytes per cached or
+ *                  whose chunk spans 16 or more tiles, or 8 or more behind 8192 or more
+ *                  cached tokens (4 x Hkv x D bytes per cached or
  *                  new token of such a sequence, 1 GiB at most: sequences beyond that
  *                  are computed from the codes); contents are undefined afterwards;
  *                  must not be shared by calls that can overlap on the device

@@ -135,7 +135,9 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
   // fp8 cache: a chunk of many tiles reads each key of its sequence that many times; its
   // K/V is then converted to bf16 once (into the workspace) and the tiles run on the bf16
   // pipeline (measured on the chunks of the 70B-shaped batch: 7.66 -> 6.6 ms of attention).
-  constexpr int kStageMinTiles = 16;
+  // (measured on 70B-shaped iterations, whole call: 16 tiles gain 5 % behind 2 k cached tokens and 14 %
+  // behind 32 k; 8 tiles lose 2 % behind 2 k and gain 10 % behind 32 k)
+  constexpr int kStageMinTiles = 16, kStageMinTilesLong = 8, kStageLongKeys = 8192;
   constexpr long long kStageMaxBytes = 1LL << 30;  // of workspace for the copy; later sequences convert on the fly
   const long long stage_block_bytes = 2LL * Hkv * kBlock * D * 2;  // K and V of one block, bf16
   const bool fp8 = cache->kv_dtype == CRONUS_KV_FP8_E4M3;
@@ -176,7 +178,8 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
         }
         Group g{(int32_t)sc.wide.size(), 0, 0.f};
         int32_t wide_tag = 1;
-        if (fp8 && (C + wide_tok - 1) / wide_tok >= kStageMinTiles) {
+        const int seq_tiles = (C + wide_tok - 1) / wide_tok;
+        if (fp8 && (seq_tiles >= kStageMinTiles || (seq_tiles >= kStageMinTilesLong && P + C >= kStageLongKeys))) {
           const int32_t nb = (P + C + kBlock - 1) / kBlock;
           const bool listed = !sc.stages.empty() && sc.stages.back().seq == s;
           if (!listed && (n_stage_blocks + nb) * stage_block_bytes <= kStageMaxBytes) {
