@@ -16,8 +16,9 @@
 //                 bf16 copy of its sequence that kv_stage_kernel makes first, through the
 //                 same DMA pipeline as a bf16 cache.
 //   narrow item - at most 32 rows (a decode, or a short chunk) against a span of
-//                 keys; the 8 waves split the span and stream K/V chunks from the
-//                 paged pools through private LDS planes.
+//                 keys; the 8 waves split the span and stream K/V from the paged pools
+//                 through private LDS (bf16: the chunk each lane needs, 16 bytes; fp8:
+//                 whole blocks, from which the lanes pick their 8-byte chunks).
 // Items that cover a span only leave (O, m, l) partial results, which the merge kernel
 // combines.
 //
@@ -760,11 +761,27 @@ __device__ __forceinline__ void run_wide_dma(const AttnParams& p, const WorkItem
 }
 
 // --------------------------------------------------------- narrow (decode-like) item
-template <int D, bool FP8>
-struct NarrowOps {
-  typename RawChunk<FP8>::type k[D / 16];
-  typename RawChunk<FP8>::type v[2 * (D / 32)];
-};
+// Operand chunks of 8 bytes picked out of a block image in LDS (fp8 codes).
+template <int O0, int O1, int O2, int O3, int O4, int O5, int O6, int O7>
+__device__ __forceinline__ void lds_read8_b64(u32x2 (&x)[8], unsigned addr) {
+  asm volatile(
+      "ds_read_b64 %0, %8 offset:%9\n\tds_read_b64 %1, %8 offset:%10\n\t"
+      "ds_read_b64 %2, %8 offset:%11\n\tds_read_b64 %3, %8 offset:%12\n\t"
+      "ds_read_b64 %4, %8 offset:%13\n\tds_read_b64 %5, %8 offset:%14\n\t"
+      "ds_read_b64 %6, %8 offset:%15\n\tds_read_b64 %7, %8 offset:%16\n\ts_waitcnt lgkmcnt(0)"
+      : "=&v"(x[0]), "=&v"(x[1]), "=&v"(x[2]), "=&v"(x[3]), "=&v"(x[4]), "=&v"(x[5]), "=&v"(x[6]), "=&v"(x[7])
+      : "v"(addr), "i"(O0), "i"(O1), "i"(O2), "i"(O3), "i"(O4), "i"(O5), "i"(O6), "i"(O7)
+      : "memory");
+}
+template <int O0, int O1, int O2, int O3>
+__device__ __forceinline__ void lds_read4_b64(u32x2 (&x)[4], unsigned addr) {
+  asm volatile(
+      "ds_read_b64 %0, %4 offset:%5\n\tds_read_b64 %1, %4 offset:%6\n\t"
+      "ds_read_b64 %2, %4 offset:%7\n\tds_read_b64 %3, %4 offset:%8\n\ts_waitcnt lgkmcnt(0)"
+      : "=&v"(x[0]), "=&v"(x[1]), "=&v"(x[2]), "=&v"(x[3])
+      : "v"(addr), "i"(O0), "i"(O1), "i"(O2), "i"(O3)
+      : "memory");
+}
 
 // Read the NOPS 1-KiB operand planes of this lane (plane n at addr + 1024 n).
 template <int NOPS>
@@ -779,7 +796,7 @@ __device__ __forceinline__ void run_narrow(const AttnParams& p, const WorkItem& 
   constexpr int NSTEP = D / 16, NDB = D / 32;
   constexpr int ESZ = FP8 ? 1 : 2;
   constexpr int NACC = NDB * 16;
-  constexpr int WAVE_LDS = 2 * NSTEP * 1024;  // per-wave LDS: K planes then V planes (= NACC * 256)
+  constexpr int WAVE_LDS = 2 * NSTEP * 1024 + (FP8 ? 512 : 0);  // per-wave LDS: K planes then V planes (= NACC * 256); fp8: two sets of block images
   using Raw = typename RawChunk<FP8>::type;
 
   const int tid = threadIdx.x;
@@ -916,43 +933,79 @@ __device__ __forceinline__ void run_narrow(const AttnParams& p, const WorkItem& 
       if (has_next) issue_v(j + 1);
     }
   } else {
-    // fp8: chunks are 8 bytes; two operand sets in registers, converted when consumed
-    auto load_ops = [&](NarrowOps<D, FP8>& ops, int u) {
-      if (u >= n_sub) return;
-      const int blk0 = (it.kv_begin + 32 * u) >> 4;
-      const unsigned char* kp =
-          p.k_pool + ((long long)bt[min(blk0 + (pr >> 4), last_blk)] * p.n_kv_heads + it.kv_head) * head_stride + k_lane_off;
+    // fp8: the two blocks of a sub-tile are copied whole, 16 bytes per lane, into block
+    // images in this wave's LDS (K: 2 x 16*D bytes, the second image 128 bytes further so
+    // that the two halves of a read hit different banks; V: 2 x 16*D bytes); the operand
+    // chunks are picked out of the images with 8-byte reads and converted.  Two sets: the
+    // sub-tile after next is requested as soon as a set has been read.
+    constexpr int BLKB = 16 * D;                 // bytes of one (block, head) of codes
+    constexpr int NIB = BLKB / 1024;             // transfers per block
+    constexpr int NIK = 2 * NIB;                 // transfers of K (and of V) per sub-tile
+    constexpr int KSET = 2 * BLKB + 128, SET = KSET + 2 * BLKB;
+    static_assert(2 * SET <= WAVE_LDS, "two sets per wave");
+    lds_byte* wl = (lds_byte*)smem + wave * WAVE_LDS;
+    const unsigned wl_addr = (unsigned)(unsigned long long)wl;
+    const unsigned k_rd = wl_addr + (pr >> 4) * (BLKB + 128) + (half * 16 + (pr & 15)) * 8;
+    const unsigned v_rd = wl_addr + KSET + (half * D + pr) * 8;
+    int bt_reg = 0;
+    auto load_table = [&](int j0) {
+      const int uu = wave + kWaves * (j0 + (lane >> 1));
+      bt_reg = bt[min(((it.kv_begin + 32 * uu) >> 4) + (lane & 1), last_blk)];
+      asm volatile("" : "+v"(bt_reg));
+    };
+    auto issue = [&](int j) {
+      if ((j & 31) == 0) load_table(j);
+      lds_byte* set = wl + (j & 1) * SET;
 #pragma unroll
-      for (int s = 0; s < NSTEP; ++s) ops.k[s] = load_chunk<FP8>(kp + s * (256 * ESZ));
+      for (int blk = 0; blk < 2; ++blk) {
+        const long long b = __builtin_amdgcn_readlane(bt_reg, 2 * (j & 31) + blk);
+        const unsigned char* g = p.k_pool + (b * p.n_kv_heads + it.kv_head) * BLKB + lane * 16;
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const unsigned char* vp =
-            p.v_pool + ((long long)bt[min(blk0 + t, last_blk)] * p.n_kv_heads + it.kv_head) * head_stride + v_lane_off;
+        for (int i = 0; i < NIB; ++i)
+          __builtin_amdgcn_global_load_lds(g + i * 1024, set + blk * (BLKB + 128) + i * 1024, 16, 0, 0);
+      }
 #pragma unroll
-        for (int db = 0; db < NDB; ++db) ops.v[t * NDB + db] = load_chunk<FP8>(vp + db * (256 * ESZ));
+      for (int blk = 0; blk < 2; ++blk) {
+        const long long b = __builtin_amdgcn_readlane(bt_reg, 2 * (j & 31) + blk);
+        const unsigned char* g = p.v_pool + (b * p.n_kv_heads + it.kv_head) * BLKB + lane * 16;
+#pragma unroll
+        for (int i = 0; i < NIB; ++i)
+          __builtin_amdgcn_global_load_lds(g + i * 1024, set + KSET + blk * BLKB + i * 1024, 16, 0, 0);
       }
     };
-    auto consume = [&](const NarrowOps<D, FP8>& ops, int u) {
+    auto read_k = [&](u32x4 (&x)[NSTEP], int j) {
+      u32x2 r[NSTEP];
+      const unsigned a = k_rd + (j & 1) * SET;
+      if constexpr (NSTEP == 8) lds_read8_b64<0, 256, 512, 768, 1024, 1280, 1536, 1792>(r, a);
+      else lds_read4_b64<0, 256, 512, 768>(r, a);
+#pragma unroll
+      for (int n = 0; n < NSTEP; ++n) x[n] = fp8x8_to_bf16x8(r[n]);
+    };
+    auto read_v = [&](u32x4 (&x)[NSTEP], int j) {
+      u32x2 r[NSTEP];
+      const unsigned a = v_rd + (j & 1) * SET;
+      if constexpr (NSTEP == 8) lds_read8_b64<0, 256, 512, 768, BLKB, BLKB + 256, BLKB + 512, BLKB + 768>(r, a);
+      else lds_read4_b64<0, 256, BLKB, BLKB + 256>(r, a);
+#pragma unroll
+      for (int n = 0; n < NSTEP; ++n) x[n] = fp8x8_to_bf16x8(r[n]);
+    };
+    const int n_iter = n_sub > wave ? (n_sub - wave + kWaves - 1) / kWaves : 0;
+    if (n_iter > 0) issue(0);
+    if (n_iter > 1) issue(1);
+    pin_q();
+    for (int j = 0; j < n_iter; ++j) {
+      const int u = wave + kWaves * j;
+      const bool more = j + 1 < n_iter;  // sub-tile j + 1 has been requested
       u32x4 kop[NSTEP], vop[NSTEP], pp[2];
       f32x16 s;
-#pragma unroll
-      for (int i = 0; i < NSTEP; ++i) kop[i] = to_bf16_chunk<FP8>(ops.k[i]);
+      if (more) wait_vmcnt<3 * NIK>(); else wait_vmcnt<NIK>();   // K(j) landed
+      read_k(kop, j);
       compute_s(kop, s);
       softmax(s, pp, u);
-#pragma unroll
-      for (int i = 0; i < NSTEP; ++i) vop[i] = to_bf16_chunk<FP8>(ops.v[i]);
+      if (more) wait_vmcnt<2 * NIK>(); else wait_vmcnt<0>();     // V(j) landed
+      read_v(vop, j);
+      if (j + 2 < n_iter) issue(j + 2);                          // this set is free again
       compute_pv(vop, pp, u);
-    };
-    NarrowOps<D, FP8> a, b;
-    load_ops(a, wave);
-    pin_q();
-    for (int u = wave; u < n_sub; u += 2 * kWaves) {
-      load_ops(b, u + kWaves);
-      consume(a, u);
-      if (u + kWaves < n_sub) {
-        load_ops(a, u + 2 * kWaves);
-        consume(b, u + kWaves);
-      }
     }
   }
 
@@ -1104,7 +1157,7 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(AttnParams p)
 template <int D, bool FP8>
 int launch_typed(const AttnLaunch& a, const AttnParams& p) {
   constexpr int wide_lds = 4 * 2 * 4 * 16 * D * 2;  // stages x (K + V tile of 64 keys)
-  constexpr int narrow_lds = kWaves * (2 * (D / 16) * 1024) + kWaves * 2 * 64 * 4;
+  constexpr int narrow_lds = kWaves * (2 * (D / 16) * 1024 + (FP8 ? 512 : 0)) + kWaves * 2 * 64 * 4;
   constexpr int lds = wide_lds > narrow_lds ? wide_lds : narrow_lds;
   static_assert(lds <= 160 * 1024, "LDS budget");
   hipStream_t s = static_cast<hipStream_t>(a.stream);
