@@ -28,14 +28,17 @@ What is computed
 * ``fp8_e4m3_encode`` / ``fp8_e4m3_decode``: software OCP e4m3 quantiser
   (round-to-nearest-even, saturating at +-448).  This format is not in the paper; it
   belongs to the 70B-shaped workload only.
-* ``balancer_split``: Algorithm 1 with Eq. 1-3, as printed (appendix A).
+* ``balancer_table`` / ``balancer_split``: Algorithm 1 with Eq. 1-3, as printed
+  (appendix A): the per-candidate table and the split it selects.
 
 Pins (tests/test_oracle_pins.py): split-anywhere equals unsplit prefill, rows of
 softmax weights sum to one, a scalar brute force, closed forms (L = 1, constant V,
 equal keys -> running mean), shift invariance, one-hot limit, decode == chunk of 1,
 GQA == MHA with repeated heads, torch's scaled_dot_product_attention in fp64,
 scatter/gather inverse with sentinel check, all 256 fp8 codes round trip, fp8
-midpoints to even, torch.float8_e4m3fn casts, Algorithm 1 against exhaustive search.
+midpoints to even, torch.float8_e4m3fn casts; Algorithm 1: candidate tables worked by
+hand (tests/golden/balancer_alg1_cases.txt), linearity of the modelled times inside an
+iteration-count class, exhaustive search over the candidates.
 """
 from __future__ import annotations
 
@@ -241,19 +244,23 @@ def fp8_e4m3_encode(x_f32: np.ndarray, scale_f32) -> np.ndarray:
 
 
 # ------------------------------------------------------------- Algorithm 1 / Eq. 1-3
-def balancer_split(l_in, n_d, l_ctxd, n_free, k_p, b_p, k_ctxp, k_ctxd, b_c,
-                   n_size=BLOCK, batch_tokens=512, n_candidates=512):
-    """Partial prefill length chosen by Algorithm 1 (appendix A) with Eq. 2 and Eq. 3.
+def balancer_table(l_in, n_d, l_ctxd, k_p, b_p, k_ctxp, k_ctxd, b_c, batch_tokens=512, n_candidates=512):
+    """The candidate table of Algorithm 1 (appendix A): one row per candidate j = 1 ..
+    n_candidates, (L_p, N_iter, L_last, T_prefill, T_chunked), in the algorithm's order.
 
-    Reading of the garbled symbols: n_d = number of decode requests on the chunked
-    prefill instance, l_ctxd = sum of their context lengths, n_free = its free KV
-    blocks.  The printed T_chunked uses (L_in + L_last)/2 as the mean prefill
-    context, which is kept as printed.
+    L_p = ceil(j / n_candidates * L_in); T_prefill from Eq. 2; n_p = B - n_d prefill tokens
+    per iteration; L_c = L_in - L_p tokens are left for the chunked prefill instance, which
+    needs N_iter = ceil(L_c / n_p) iterations, the last of them with prefill context
+    L_last = L_p + floor(L_c / n_p) * n_p; T_chunked is N_iter times the Eq. 3 iteration time
+    at the mean context (L_in + L_last) / 2, as the algorithm prints it (Eq. 1 states the mean
+    of the first and last iteration times; the printed form is kept).
     """
-    if n_free < -(-l_in // n_size):
-        return l_in
-    best, best_gap = None, None
+    if not 0 <= n_d < batch_tokens:
+        raise ValueError("n_d must lie in [0, batch_tokens): an iteration needs at least one prefill token")
+    if l_in <= 0 or n_candidates <= 0:
+        raise ValueError("l_in and n_candidates must be positive")
     n_p = batch_tokens - n_d
+    rows = []
     for j in range(1, n_candidates + 1):
         l_p = -(-j * l_in // n_candidates)  # ceil(j/512 * L_in) in integers
         t_prefill = k_p * l_p + b_p
@@ -261,6 +268,27 @@ def balancer_split(l_in, n_d, l_ctxd, n_free, k_p, b_p, k_ctxp, k_ctxd, b_c,
         n_iter = -(-l_c // n_p)
         l_last = l_p + (l_c // n_p) * n_p
         t_chunked = n_iter * (k_ctxp * (l_in + l_last) / 2.0 + k_ctxd * l_ctxd + b_c)
+        rows.append((l_p, n_iter, l_last, t_prefill, t_chunked))
+    return rows
+
+
+def balancer_split(l_in, n_d, l_ctxd, n_free, k_p, b_p, k_ctxp, k_ctxd, b_c,
+                   n_size=BLOCK, batch_tokens=512, n_candidates=512):
+    """Partial prefill length chosen by Algorithm 1 (appendix A) with Eq. 2 and Eq. 3.
+
+    Reading of the garbled symbols: n_d = number of decode requests on the chunked
+    prefill instance, l_ctxd = sum of their context lengths, n_free = its free KV
+    blocks.  The printed T_chunked uses (L_in + L_last)/2 as the mean prefill
+    context, which is kept as printed.  Too few free blocks for the whole prompt:
+    the prompt is prefilled entirely on the partial prefill instance (L_p = L_in).
+    """
+    if not 0 <= n_d < batch_tokens:
+        raise ValueError("n_d must lie in [0, batch_tokens): an iteration needs at least one prefill token")
+    if n_free < -(-l_in // n_size):
+        return l_in
+    best, best_gap = None, None
+    for l_p, _, _, t_prefill, t_chunked in balancer_table(l_in, n_d, l_ctxd, k_p, b_p, k_ctxp, k_ctxd, b_c,
+                                                          batch_tokens, n_candidates):
         gap = abs(t_prefill - t_chunked)
         if best_gap is None or gap < best_gap:  # argmin takes the first minimum
             best, best_gap = l_p, gap

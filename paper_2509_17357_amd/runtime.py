@@ -66,11 +66,13 @@ class DeviceIteration:
         self.workspace_bytes = 0
 
     # ---- inputs
-    def load_host_inputs(self):
+    def load_host_inputs(self, kv=None):
         """Tensors drawn on the host by the seeded generators (bit-identical to what the
-        oracle side sees).  Returns the per-sequence (k_bits, v_bits) for the caller."""
+        oracle side sees).  Returns the per-sequence (k_bits, v_bits) for the caller, who
+        may also pass them in (drawn already, e.g. by several threads)."""
         b = self.batch
-        kv = [b.gen_kv(s) for s in range(b.n_seqs)]
+        if kv is None:
+            kv = [b.gen_kv(s) for s in range(b.n_seqs)]
         P = b.prefix_lens
         sh = b.shape
         empty = np.zeros((0, sh.n_kv_heads, sh.head_dim), dtype=np.uint16)

@@ -215,30 +215,53 @@ def custom_batch(shape: HeadShape, prefix_lens, chunk_lens, seed: int, name="cus
 
 def stress_qkv(kind: str, seed: int, C: int, L: int, shape: HeadShape):
     """Inputs outside the benign N(0,1)/8 regime, as bf16 bits (q [C,Hq,D], k, v [L,Hkv,D]).
+    The C query rows sit at positions L-C .. L-1, so keys 0 .. L-C are visible to all of them.
 
-    peaky     : Q x 16, sharply peaked softmax
-    outlier   : one key per kv head with a huge logit against every query
-    monotone  : logits increasing with key position (running max changes at every key)
-    equal     : all keys identical (uniform weights over the visible keys)
+    peaky         : Q x 16, sharply peaked softmax
+    outlier       : one key per kv head (random position) with a huge logit against every query
+    outlier_last  : that key sits three keys before the first query row's causal end: it arrives
+                    late in every row's stream of keys (in the last span of a split item)
+    outlier_first : that key is key 2: the peak lies in the first span only
+    monotone      : logits increasing gently with key position (about 20 bits over the context)
+    ramp_up       : logits rising by about 7 bits per 32 keys (the running maximum outgrows any
+                    reference within two sub-tiles, all the way through the context)
+    ramp_down     : the same ramp falling: the maximum comes first, later weights underflow
+    equal         : all keys identical (uniform weights over the visible keys)
     """
     rng = np.random.default_rng([seed, 0x57])
     Hq, Hkv, D = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
     q = rng.standard_normal((C, Hq, D), dtype=np.float32) * np.float32(0.125)
-    k = rng.standard_normal((L, Hkv, D), dtype=np.float32) * np.float32(0.125)
-    v = rng.standard_normal((L, Hkv, D), dtype=np.float32) * np.float32(0.125)
+    # random K/V rows are drawn for at most 2048 keys and repeated along a longer context (cheap
+    # at 100 k keys); everything is assembled as bf16 bit patterns, never as fp32 of full length
+    base = min(L, 2048)
+    draw = lambda: np.resize(f32_to_bf16_bits(rng.standard_normal((base, Hkv, D), dtype=np.float32) * np.float32(0.125)),
+                             (L, Hkv, D))
+    k, v = draw(), draw()
+    per_key = lambda t: np.broadcast_to(f32_to_bf16_bits(t.astype(np.float32))[:, None, None], (L, Hkv, D)).copy()
     if kind == "peaky":
         q *= np.float32(16.0)
-    elif kind == "outlier":
+    elif kind in ("outlier", "outlier_last", "outlier_first"):
         q = np.abs(q) + np.float32(0.25)
-        j = rng.integers(0, L, size=Hkv)
+        if kind == "outlier":
+            j = rng.integers(0, L, size=Hkv)
+        elif kind == "outlier_last":
+            j = np.full(Hkv, max(L - C - 3, 0))
+        else:
+            j = np.full(Hkv, min(2, L - 1))
         for g in range(Hkv):
-            k[j[g], g, :] = np.float32(4.0)
+            k[j[g], g, :] = f32_to_bf16_bits(np.float32(4.0))
     elif kind == "monotone":
         q = np.abs(q) + np.float32(0.5)
-        ramp = (np.arange(L, dtype=np.float32) / np.float32(max(L - 1, 1)))[:, None, None]
-        k = np.broadcast_to(ramp * np.float32(2.0), (L, Hkv, D)).copy()
+        k = per_key(np.arange(L, dtype=np.float32) / np.float32(max(L - 1, 1)) * np.float32(2.0))
+    elif kind in ("ramp_up", "ramp_down"):
+        # q = 4 in every dim, k = t(j) in every dim: logit = sm_scale * 4 D t(j); in log2 units
+        # (x log2 e, sm_scale = 1/sqrt(D)) a slope of 7/32 per key needs t' = 7 / (32 * 4 * sqrt(D) * 1.4427)
+        q = np.full((C, Hq, D), 4.0, dtype=np.float32)
+        step = np.float32(7.0 / (32.0 * 4.0 * np.sqrt(D) * 1.4427))
+        pos = np.arange(L, dtype=np.float32)
+        k = per_key((pos[::-1] if kind == "ramp_down" else pos) * step)
     elif kind == "equal":
         k = np.broadcast_to(k[:1], (L, Hkv, D)).copy()
     else:
         raise ValueError(kind)
-    return f32_to_bf16_bits(q), f32_to_bf16_bits(k), f32_to_bf16_bits(v)
+    return f32_to_bf16_bits(q), k, v

@@ -1,6 +1,9 @@
-"""Prefix ingest on a side stream while the attention of other requests runs (section 4.2):
-the attention output must be bit-identical to the one computed with nothing else running,
-and the newcomers' prefixes must sit in their blocks bit for bit afterwards."""
+"""Prefix ingest on a side stream while the attention of other requests runs (section 4.2,
+steps 6-7: the transferred KV cache is stored while the instance keeps computing).  The
+attention output must match the fp64 oracle and be bit-identical to the one computed with
+nothing else running; afterwards both pools must equal the reference scatter's image bit for
+bit (the running requests' rows, the newcomers' prefixes, untouched slots), and the gather
+must return the newcomers' prefixes."""
 import numpy as np
 import pytest
 import torch
@@ -9,6 +12,8 @@ from paper_2509_17357_amd import binding as B
 from paper_2509_17357_amd import workloads as W
 from paper_2509_17357_amd.overlap import OverlapRun
 from paper_2509_17357_amd.runtime import bits_from_bf16_tensor
+
+import parity_util as U
 
 pytestmark = pytest.mark.gpu
 
@@ -22,6 +27,13 @@ def test_overlapped_ingest_leaves_attention_untouched(source):
     run.attention(main)
     torch.cuda.synchronize()
     ref = run.out_run.clone()
+    # the reference run itself against the oracle (the running requests only)
+    sub = W.custom_batch(batch.shape, run.P_run, run.C_run, seed=1)
+    want = U.oracle_attention(sub, bits_from_bf16_tensor(run.q_run), U.oracle_kv_values(sub, run.kv_bits[:run.n_run]),
+                              it.sm_scale)
+    rep = U.error_report(sub, bits_from_bf16_tensor(ref), want)
+    print(source, rep)
+    U.assert_within_tolerance(rep)
     # wipe the newcomers' blocks, then ingest them again while the attention runs (several rounds)
     ids = torch.from_numpy(np.concatenate([batch.block_tables[s][:(batch.prefix_lens[s] + 16) // 16]
                                            for s in range(run.n_run, batch.n_seqs)]).astype(np.int64)).to(it.device)
@@ -36,7 +48,18 @@ def test_overlapped_ingest_leaves_attention_untouched(source):
         run.attention(main)
         torch.cuda.synchronize()
         assert torch.equal(run.out_run, ref)
-    # the prefixes are back: export them through the gather and compare with the source bits
+    # both pools against the reference scatter: the running requests hold prefix + new rows,
+    # the newcomers their prefix rows only (their blocks were wiped with the fill pattern)
+    import dataclasses
+    C_after = batch.chunk_lens.copy()
+    C_after[run.n_run:] = 0
+    after = dataclasses.replace(batch, chunk_lens=C_after)
+    kv_after = [(k, v) if s < run.n_run else (k[:batch.prefix_lens[s]], v[:batch.prefix_lens[s]])
+                for s, (k, v) in enumerate(run.kv_bits)]
+    kp, vp = U.oracle_pools(after, kv_after, fill=0x7FC1)
+    assert np.array_equal(it.k_pool.cpu().numpy().view(np.uint16), kp), "K pool differs from the reference scatter"
+    assert np.array_equal(it.v_pool.cpu().numpy().view(np.uint16), vp), "V pool differs from the reference scatter"
+    # and the prefixes come back through the gather, bit for bit
     P_new = batch.prefix_lens[run.n_run:].astype(np.int64)
     n = int(P_new.sum())
     sh = batch.shape

@@ -305,32 +305,50 @@ def test_fp8_against_torch_cast_in_range():
 
 
 # ----------------------------------------------------------------- Algorithm 1
-def _t_chunked(l_in, l_p, n_d, l_ctxd, k_ctxp, k_ctxd, b_c, B=512):
-    n_p = B - n_d
-    l_c = l_in - l_p
-    n_iter = -(-l_c // n_p)
-    l_last = l_p + (l_c // n_p) * n_p
-    return n_iter * (k_ctxp * (l_in + l_last) / 2 + k_ctxd * l_ctxd + b_c)
+# The arithmetic of the candidate table is pinned by hand-worked cases in
+# tests/test_balancer_golden_cpu.py; here: the selection rule and structural properties,
+# read off the oracle's own table (no formula of the method is restated).
+COEF = dict(k_p=2.0e-4, b_p=5e-3, k_ctxp=2.0e-6, k_ctxd=1.0e-7, b_c=3e-2)
 
 
 def test_balancer_capacity_fallback_and_argmin():
-    coef = dict(k_p=2.0e-4, b_p=5e-3, k_ctxp=2.0e-6, k_ctxd=1.0e-7, b_c=3e-2)
     # not enough free blocks: whole prompt is prefilled on the low-end GPU (Algorithm 1, first branch)
-    assert orc.balancer_split(1000, 10, 5000, n_free=62, **coef) == 1000
-    assert orc.balancer_split(1000, 10, 5000, n_free=63, **coef) < 1000
-    # L_in <= 512: the candidates are every length 1..L_in, so the result is the exhaustive argmin
-    for l_in in (37, 200, 512):
-        got = orc.balancer_split(l_in, 12, 30000, n_free=10 ** 6, **coef)
-        gaps = [abs(coef["k_p"] * lp + coef["b_p"] - _t_chunked(l_in, lp, 12, 30000, coef["k_ctxp"], coef["k_ctxd"],
-                                                                coef["b_c"])) for lp in range(1, l_in + 1)]
-        assert got == 1 + int(np.argmin(gaps))
-    # longer prompts: result is one of the 512 candidates and no candidate does better
-    l_in = 3000
-    got = orc.balancer_split(l_in, 40, 10 ** 5, n_free=10 ** 6, **coef)
-    cands = sorted({-(-j * l_in // 512) for j in range(1, 513)})
-    assert got in cands
-    gap = lambda lp: abs(coef["k_p"] * lp + coef["b_p"] - _t_chunked(l_in, lp, 40, 10 ** 5, coef["k_ctxp"],
-                                                                     coef["k_ctxd"], coef["b_c"]))
-    assert all(gap(got) <= gap(c) for c in cands)
-    # L_p = L_in (disaggregated limit): zero chunked iterations, T_chunked = 0
-    assert _t_chunked(l_in, l_in, 40, 10 ** 5, 1, 1, 1) == 0
+    assert orc.balancer_split(1000, 10, 5000, n_free=62, **COEF) == 1000
+    assert orc.balancer_split(1000, 10, 5000, n_free=63, **COEF) < 1000
+    for l_in, n_d, l_ctxd in ((37, 12, 30000), (200, 12, 30000), (512, 12, 30000), (3000, 40, 10 ** 5), (50000, 500, 10 ** 6)):
+        rows = orc.balancer_table(l_in, n_d, l_ctxd, **COEF)
+        assert len(rows) == 512 and rows[-1][0] == l_in and rows[-1][1] == 0 and rows[-1][4] == 0.0
+        if l_in <= 512:  # every length 1 .. L_in is a candidate
+            assert sorted({r[0] for r in rows}) == list(range(1, l_in + 1))
+        gaps = [abs(r[3] - r[4]) for r in rows]
+        got = orc.balancer_split(l_in, n_d, l_ctxd, n_free=10 ** 6, **COEF)
+        assert got == rows[int(np.argmin(gaps))][0]      # numpy's argmin is the first minimum too
+
+
+def test_balancer_table_structure():
+    """Inside a run of candidates with the same number of iterations, one more token on the
+    partial prefill instance moves the last iteration's context by exactly one token, so both
+    modelled times are linear in L_p there; the iteration count never grows with L_p; and the
+    tokens of all iterations add up: (N_iter - 1) n_p < L_in - L_p <= N_iter n_p."""
+    l_in, n_d, l_ctxd, B_tok = 400, 112, 7000, 512   # n_p = 400: every L_p is a candidate
+    rows = orc.balancer_table(l_in, n_d, l_ctxd, **COEF, batch_tokens=B_tok)
+    rows = [r for i, r in enumerate(rows) if i == 0 or rows[i - 1][0] != r[0]]
+    n_p = B_tok - n_d
+    for (lp0, n0, last0, tp0, tc0), (lp1, n1, last1, tp1, tc1) in zip(rows, rows[1:]):
+        assert lp1 == lp0 + 1 and n1 <= n0
+        assert (n0 - 1) * n_p < l_in - lp0 <= n0 * n_p
+        assert lp0 <= last0 <= l_in
+    l_in, n_d = 3000, 12                                # n_p = 500, several iteration counts
+    rows = orc.balancer_table(l_in, n_d, 0, 1.0, 0.0, 1.0, 0.0, 0.0, n_candidates=3000)
+    by_n = {}
+    for r in rows:
+        by_n.setdefault(r[1], []).append(r)
+    assert sorted(by_n) == [0, 1, 2, 3, 4, 5, 6]
+    for n, rs in by_n.items():
+        if n == 0 or len(rs) < 3:
+            continue
+        # drop the one candidate of the class whose remainder is a whole number of iterations
+        # (there the printed L_last jumps to L_in), the rest is an arithmetic sequence
+        inner = [r for r in rs if (l_in - r[0]) % 500]
+        d = [b[4] - a[4] for a, b in zip(inner, inner[1:])]
+        assert max(d) - min(d) < 1e-9 and abs(d[0] - n * 0.5) < 1e-9   # slope N_iter * k_ctxp / 2
