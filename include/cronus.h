@@ -24,7 +24,14 @@
  *     is the default stream).  No call synchronises the device.  Host arrays are
  *     consumed before the call returns.
  *   - Return value: a cronus_status.  Arguments are checked on the host before
- *     anything is launched; on error nothing has been enqueued.
+ *     anything is launched: INVALID_ARG, UNSUPPORTED and WORKSPACE mean that nothing has
+ *     been enqueued.  CRONUS_ERR_HIP reports a failed HIP runtime call; one-time set-up
+ *     (kernel attributes, the plan buffers) precedes the first launch of a call, but a
+ *     failed launch or event record can leave earlier kernels of the same call enqueued,
+ *     and the outputs of that call are then undefined.
+ *   - Device-side facts (CU count, kernel set-up, plan buffers) are kept per device and
+ *     looked up for the device that is current in the calling thread; calls are
+ *     serialised by one lock.
  *   - Block ids in block tables are NOT checked on the device: an id outside
  *     [0, num_blocks) or two rows mapped to one slot in a single call is undefined
  *     behaviour.  Table entries past ceil(len/16) are never read and may hold
@@ -116,8 +123,8 @@ int cronus_kv_append(const cronus_kv_cache* cache, const void* k_src, const void
  *   chunk_lens   : host, int32 [n_seqs]
  *   block_tables : device, int32 [n_seqs][max_blocks_per_seq]
  *   sm_scale     : softmax scale, normally 1/sqrt(D)
- *   workspace    : device, at least cronus_attn_mixed_workspace_bytes() bytes, 256-byte
- *                  aligned; holds the partial results of key spans until they are
+ *   workspace    : device, at least cronus_attn_mixed_workspace_bytes() bytes (never 0),
+ *                  256-byte aligned; holds the partial results of key spans until they are
  *                  merged and, for an fp8 cache, a bf16 copy of the K/V of every sequence
  *                  whose chunk spans 16 or more tiles, or 8 or more behind 8192 or more
  *                  cached tokens (4 x Hkv x D bytes per cached or
@@ -142,9 +149,11 @@ size_t cronus_attn_mixed_workspace_bytes(const cronus_kv_cache* cache, const int
 
 /*
  * cronus_attn_mixed_plan_stats - how the work decomposition (mixed batch of section
- * 4.4 turned into tiles) would look for these lengths.  stats (host, int64[4]):
+ * 4.4 turned into tiles) would look for these lengths.  stats (host, int64[6]):
  * [0] work items launched, [1] of those that are wide (chunk) tiles, [2] split partial
- * results, [3] rows merged from partials.  Returns a cronus_status.
+ * results, [3] rows merged from partials, [4] work-groups of the merge kernel (0: it is
+ * not launched), [5] cache blocks converted by the fp8 copy kernel (0: it is not
+ * launched).  Returns a cronus_status.
  */
 int cronus_attn_mixed_plan_stats(const cronus_kv_cache* cache, const int32_t* prefix_lens,
                                  const int32_t* chunk_lens, int32_t n_seqs, int64_t* stats);
@@ -229,15 +238,20 @@ int cronus_balancer_split(const cronus_balancer_model* model, int64_t l_in, int6
                           double* t_chunked);
 
 /*
- * cronus_profile_events - measurement aid.  While both handles (hipEvent_t cast to
- * void*, created by the caller with timing enabled) are set, every cronus_attn_mixed
- * launches its main attention kernel with them as the start and stop events of that
- * dispatch (hipExtLaunchKernel), on that call's stream; hipEventElapsedTime(start, stop)
- * is then the duration of that one kernel launch (within a few microseconds of what a
- * profiler's kernel trace shows for it).  Pass NULL, NULL to switch it off (the default).
- * Process-wide; not meant for concurrent callers.
+ * cronus_profile_events - measurement aid.  Handles are hipEvent_t cast to void*, created
+ * by the caller with timing enabled.  While main_start and main_stop are set, every
+ * cronus_attn_mixed launches its main attention kernel with them as the start and stop
+ * events of that dispatch (hipExtLaunchKernel), on that call's stream:
+ * hipEventElapsedTime(main_start, main_stop) is then the duration of that one kernel (within
+ * a few microseconds of what a profiler's kernel trace shows for it).  A call may launch two
+ * more kernels: the fp8 copy before the main kernel (cronus_attn_mixed_plan_stats [5] > 0) and
+ * the merge after it ([4] > 0).  first_start, if set, becomes the start event of the copy
+ * kernel when there is one, and last_stop the stop event of the merge kernel when there is
+ * one; otherwise they are left untouched.  The whole attention of a call thus spans from
+ * (copy ? first_start : main_start) to (merge ? last_stop : main_stop).  Pass four NULLs to
+ * switch it off (the default).  Process-wide; not meant for concurrent callers.
  */
-void cronus_profile_events(void* start_event, void* stop_event);
+void cronus_profile_events(void* main_start, void* main_stop, void* first_start, void* last_stop);
 
 /* Static, NUL-terminated description of a cronus_status. */
 const char* cronus_status_string(int status);

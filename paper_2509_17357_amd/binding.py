@@ -78,7 +78,7 @@ def lib() -> ctypes.CDLL:
         L.cronus_attn_mixed_plan_stats.restype = ctypes.c_int
         L.cronus_attn_mixed_plan_items.argtypes = [cp, i32p, i32p, i32, i32p, ctypes.c_int64]
         L.cronus_attn_mixed_plan_items.restype = ctypes.c_int64
-        L.cronus_profile_events.argtypes = [vp, vp]
+        L.cronus_profile_events.argtypes = [vp, vp, vp, vp]
         L.cronus_profile_events.restype = None
         L.cronus_status_string.argtypes = [ctypes.c_int]
         L.cronus_status_string.restype = ctypes.c_char_p
@@ -96,8 +96,12 @@ def version() -> int:
     return lib().cronus_version()
 
 
-def cronus_profile_events(start_event: int | None, stop_event: int | None) -> None:
-    lib().cronus_profile_events(ctypes.c_void_p(start_event), ctypes.c_void_p(stop_event))
+def cronus_profile_events(main_start: int | None, main_stop: int | None, first_start: int | None = None,
+                          last_stop: int | None = None) -> None:
+    """Events of the main kernel's dispatch; optionally the start of the call's first kernel
+    (when that is the fp8 copy) and the stop of its last kernel (when that is the merge)."""
+    lib().cronus_profile_events(ctypes.c_void_p(main_start), ctypes.c_void_p(main_stop),
+                                ctypes.c_void_p(first_start), ctypes.c_void_p(last_stop))
 
 
 class HipEvents:
@@ -196,11 +200,12 @@ def cronus_attn_mixed_workspace_bytes(cache: cronus_kv_cache, prefix_lens, chunk
 def cronus_attn_mixed_plan_stats(cache: cronus_kv_cache, prefix_lens, chunk_lens) -> dict:
     p, pp = _host_i32(prefix_lens)
     c, cp = _host_i32(chunk_lens)
-    st = (ctypes.c_int64 * 4)()
+    st = (ctypes.c_int64 * 6)()
     rc = lib().cronus_attn_mixed_plan_stats(ctypes.byref(cache), pp, cp, int(p.size), st)
     if rc != CRONUS_OK:
         raise CronusError(rc, "cronus_attn_mixed_plan_stats")
-    return {"items": st[0], "wide_items": st[1], "partials": st[2], "merge_rows": st[3]}
+    return {"items": st[0], "wide_items": st[1], "partials": st[2], "merge_rows": st[3], "merge_groups": st[4],
+            "copy_blocks": st[5]}
 
 
 PLAN_ITEM_FIELDS = ("seq", "kv_head", "head0", "n_heads", "q_tok0", "n_tok", "kv_begin", "kv_end", "partial", "wide",

@@ -38,18 +38,43 @@ int check_shape(const cronus_kv_cache* c) {
   return CRONUS_OK;
 }
 
+// Per-device facts and one-time set-up, guarded by g_mu.  Index = HIP device ordinal.
+struct DeviceState {
+  int n_cus = 0;           // 0: not queried yet
+  bool kernels_ready = false;
+};
+constexpr int kMaxDevices = 64;
+DeviceState g_dev[kMaxDevices];
+std::mutex g_mu;
+
+// CU count of the current device; 256 (MI355X) when sizes are queried without a device.
 int device_cus() {
-  static int cached = 0;
-  if (cached) return cached;
   int dev = 0, n = 0;
-  if (hipGetDevice(&dev) == hipSuccess &&
-      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) {
-    cached = n;
-  } else {
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
     (void)hipGetLastError();
-    return 256;  // MI355X; used when sizes are queried without a device
+    return 256;
   }
-  return cached;
+  std::lock_guard<std::mutex> lock(g_mu);
+  if (g_dev[dev].n_cus) return g_dev[dev].n_cus;
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+    (void)hipGetLastError();
+    return 256;
+  }
+  g_dev[dev].n_cus = n;
+  return n;
+}
+
+// Set-up that must precede the first launch on the current device (kernel attributes).
+// Caller holds g_mu.
+int prepare_device_locked(int* device) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return CRONUS_ERR_HIP;
+  *device = dev;
+  if (!g_dev[dev].kernels_ready) {
+    if (int rc = prepare_attn_kernels()) return rc;
+    g_dev[dev].kernels_ready = true;
+  }
+  return CRONUS_OK;
 }
 
 // The work list is written into pinned, device-mapped host memory and the kernels read it
@@ -64,17 +89,15 @@ struct Slot {
   hipEvent_t done = nullptr;
   bool pending = false;
 };
-void* g_ev_start = nullptr;
-void* g_ev_stop = nullptr;
+void* g_ev[4] = {nullptr, nullptr, nullptr, nullptr};
 
 constexpr int kSlots = 8;
-Slot g_slots[kSlots];
-int g_next = 0;
-std::mutex g_mu;
+Slot g_slots[kMaxDevices][kSlots];  // a ring per device: the events that guard reuse belong to a device
+int g_next[kMaxDevices] = {0};
 
-Slot* acquire_slot(size_t bytes) {
-  Slot* s = &g_slots[g_next];
-  g_next = (g_next + 1) % kSlots;
+Slot* acquire_slot(int dev, size_t bytes) {
+  Slot* s = &g_slots[dev][g_next[dev]];
+  g_next[dev] = (g_next[dev] + 1) % kSlots;
   if (s->pending) {
     if (hipEventSynchronize(s->done) != hipSuccess) return nullptr;
     s->pending = false;
@@ -145,6 +168,8 @@ int cronus_attn_mixed_plan_stats(const cronus_kv_cache* cache, const int32_t* pr
   stats[1] = plan.n_wide;
   stats[2] = plan.n_partials;
   stats[3] = plan.n_merge_rows;
+  stats[4] = plan.n_merge;
+  stats[5] = plan.n_stage_blocks;
   return CRONUS_OK;
 }
 
@@ -155,7 +180,7 @@ int64_t cronus_attn_mixed_plan_items(const cronus_kv_cache* cache, const int32_t
     return -CRONUS_ERR_INVALID_ARG;
   Plan plan;
   if (int rc = build_plan(cache, prefix_lens, chunk_lens, n_seqs, 0x7fffffff / kBlock, device_cus(), &plan)) return -rc;
-  std::vector<unsigned char> buf(plan.upload_bytes);
+  std::vector<unsigned char> buf(plan.image_bytes);
   write_plan(&plan, buf.data());
   const int64_t n = std::min<int64_t>(capacity, plan.n_items);
   const WorkItem* wi = reinterpret_cast<const WorkItem*>(buf.data() + plan.off_items);
@@ -193,11 +218,14 @@ int cronus_attn_mixed(const cronus_kv_cache* cache, const void* q, void* out, co
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   std::lock_guard<std::mutex> lock(g_mu);
-  Slot* slot = acquire_slot(plan.upload_bytes);
+  // everything that can fail without a launch comes first: kernel attributes, the plan buffer
+  int dev = 0;
+  if (int rc = prepare_device_locked(&dev)) return rc;
+  Slot* slot = acquire_slot(dev, plan.image_bytes);
   if (!slot) return CRONUS_ERR_HIP;
   write_plan(&plan, slot->host);
   AttnLaunch a{cache, q, out, block_tables, max_blocks_per_seq, sm_scale, workspace, slot->dev, &plan, hip_stream,
-               g_ev_start, g_ev_stop};
+               {g_ev[0], g_ev[1], g_ev[2], g_ev[3]}};
   const int rc = launch_attn(a);
   // whatever was launched may still read the slot
   if (hipEventRecord(slot->done, stream) != hipSuccess) return CRONUS_ERR_HIP;
@@ -205,9 +233,12 @@ int cronus_attn_mixed(const cronus_kv_cache* cache, const void* q, void* out, co
   return rc;
 }
 
-void cronus_profile_events(void* start_event, void* stop_event) {
-  g_ev_start = start_event;
-  g_ev_stop = stop_event;
+void cronus_profile_events(void* main_start, void* main_stop, void* first_start, void* last_stop) {
+  std::lock_guard<std::mutex> lock(g_mu);
+  g_ev[0] = main_start;
+  g_ev[1] = main_stop;
+  g_ev[2] = first_start;
+  g_ev[3] = last_stop;
 }
 
 const char* cronus_status_string(int status) {
@@ -221,6 +252,6 @@ const char* cronus_status_string(int status) {
   }
 }
 
-int cronus_version(void) { return 200; }  // 0.2.0: + cronus_kv_gather, cronus_balancer_split
+int cronus_version(void) { return 300; }  // 0.3.0: cronus_profile_events takes four events, plan_stats six numbers
 
 }  // extern "C"

@@ -1155,40 +1155,56 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(AttnParams p)
 }
 
 template <int D, bool FP8>
-int launch_typed(const AttnLaunch& a, const AttnParams& p) {
+constexpr int attn_lds_bytes() {
   constexpr int wide_lds = 4 * 2 * 4 * 16 * D * 2;  // stages x (K + V tile of 64 keys)
   constexpr int narrow_lds = kWaves * (2 * (D / 16) * 1024 + (FP8 ? 512 : 0)) + kWaves * 2 * 64 * 4;
   constexpr int lds = wide_lds > narrow_lds ? wide_lds : narrow_lds;
   static_assert(lds <= 160 * 1024, "LDS budget");
+  return lds;
+}
+
+template <int D, bool FP8>
+int prepare_typed() {
+  auto kern = attn_mixed_kernel<D, FP8>;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             attn_lds_bytes<D, FP8>()) == hipSuccess ? CRONUS_OK : CRONUS_ERR_HIP;
+}
+
+// Launches of one call, in order: the fp8 copy (if any sequence has one), the main kernel, the
+// merge (if any item was split).  prepare_attn_kernels() must have run on this device.  The
+// optional events of a.ev become start/stop events of these dispatches themselves, so their
+// differences are kernel durations without the launch latency around them.
+template <int D, bool FP8>
+int launch_typed(const AttnLaunch& a, const AttnParams& p) {
+  constexpr int lds = attn_lds_bytes<D, FP8>();
   hipStream_t s = static_cast<hipStream_t>(a.stream);
   const Plan& pl = *a.plan;
+  auto ev = [&](int i) { return static_cast<hipEvent_t>(a.ev[i]); };
+  const bool timed = a.ev[0] && a.ev[1];
   if constexpr (FP8) {
     if (pl.n_stage_blocks > 0) {
-      hipLaunchKernelGGL((kv_stage_kernel<D>), dim3((unsigned)pl.n_stage_blocks), dim3(kStageThreads), 0, s, p);
+      if (timed && a.ev[2])
+        hipExtLaunchKernelGGL((kv_stage_kernel<D>), dim3((unsigned)pl.n_stage_blocks), dim3(kStageThreads), 0, s, ev(2),
+                              nullptr, 0, p);
+      else
+        hipLaunchKernelGGL((kv_stage_kernel<D>), dim3((unsigned)pl.n_stage_blocks), dim3(kStageThreads), 0, s, p);
       if (hipGetLastError() != hipSuccess) return CRONUS_ERR_HIP;
     }
   }
   if (pl.n_items > 0) {
     auto kern = attn_mixed_kernel<D, FP8>;
-    static bool attr_set = false;
-    if (!attr_set) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
-          hipSuccess)
-        return CRONUS_ERR_HIP;
-      attr_set = true;
-    }
-    if (a.ev_start && a.ev_stop) {
-      // the events take the begin and end time stamps of this dispatch itself, so their
-      // difference is the kernel's duration without the launch latency around it
-      hipExtLaunchKernelGGL(kern, dim3((unsigned)pl.n_items), dim3(kThreads), lds, s,
-                            static_cast<hipEvent_t>(a.ev_start), static_cast<hipEvent_t>(a.ev_stop), 0, p);
-    } else {
+    if (timed)
+      hipExtLaunchKernelGGL(kern, dim3((unsigned)pl.n_items), dim3(kThreads), lds, s, ev(0), ev(1), 0, p);
+    else
       hipLaunchKernelGGL(kern, dim3((unsigned)pl.n_items), dim3(kThreads), lds, s, p);
-    }
     if (hipGetLastError() != hipSuccess) return CRONUS_ERR_HIP;
   }
   if (pl.n_merge > 0) {
-    hipLaunchKernelGGL((attn_merge_kernel<D, FP8>), dim3((unsigned)pl.n_merge), dim3(kMergeThreads), 0, s, p);
+    if (timed && a.ev[3])
+      hipExtLaunchKernelGGL((attn_merge_kernel<D, FP8>), dim3((unsigned)pl.n_merge), dim3(kMergeThreads), 0, s, nullptr,
+                            ev(3), 0, p);
+    else
+      hipLaunchKernelGGL((attn_merge_kernel<D, FP8>), dim3((unsigned)pl.n_merge), dim3(kMergeThreads), 0, s, p);
     if (hipGetLastError() != hipSuccess) return CRONUS_ERR_HIP;
   }
   return CRONUS_OK;
@@ -1197,6 +1213,13 @@ int launch_typed(const AttnLaunch& a, const AttnParams& p) {
 }  // namespace
 
 int wide_rows_for(int /*head_dim*/, int /*kv_dtype*/) { return kWaves * 32; }
+
+int prepare_attn_kernels() {
+  if (int rc = prepare_typed<128, false>()) return rc;
+  if (int rc = prepare_typed<128, true>()) return rc;
+  if (int rc = prepare_typed<64, false>()) return rc;
+  return prepare_typed<64, true>();
+}
 
 int launch_attn(const AttnLaunch& a) {
   const cronus_kv_cache& c = *a.cache;

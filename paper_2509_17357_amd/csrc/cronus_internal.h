@@ -86,9 +86,11 @@ struct Plan {
   int32_t wide_rows = 0;  // rows per wide tile (compile-time choice of the kernel instance)
   int32_t n_stage_seqs = 0;
   int64_t n_stage_blocks = 0;
-  // byte offsets inside the workspace
-  size_t off_items = 0, off_merge = 0, off_stage = 0, off_partials = 0, off_stage_k = 0, off_stage_v = 0, total_bytes = 0;
-  size_t upload_bytes = 0;  // [0, upload_bytes) is host-built metadata
+  // byte offsets inside the plan image (host-built metadata that the kernels read:
+  // [WorkItem x n_items | MergeItem x n_merge | StageSeq x n_stage_seqs]) and its size
+  size_t off_items = 0, off_merge = 0, off_stage = 0, image_bytes = 0;
+  // byte offsets inside the caller's workspace (partial results; fp8: the bf16 copy) and its size
+  size_t off_partials = 0, off_stage_k = 0, off_stage_v = 0, total_bytes = 0;
 };
 
 // Number of floats of one partial slot: O[32][D], m[32], l[32].
@@ -99,9 +101,11 @@ int wide_rows_for(int head_dim, int kv_dtype);
 
 // Builds the work decomposition (sizes and offsets into *plan; the work list itself stays
 // in a per-thread scratch).  write_plan() then copies that list into host_buf, which must
-// hold plan->upload_bytes bytes; it must follow build_plan() on the same thread.
+// hold plan->image_bytes bytes; it must follow build_plan() on the same thread.
+// allow_stage = false: an fp8 cache gets no bf16 copy (every chunk tile converts codes on
+// the fly), so the workspace holds partial results only.
 int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const int32_t* chunk_lens,
-               int32_t n_seqs, int32_t max_blocks_per_seq, int n_cus, Plan* plan);
+               int32_t n_seqs, int32_t max_blocks_per_seq, int n_cus, Plan* plan, bool allow_stage = true);
 void write_plan(const Plan* plan, void* host_buf);
 
 struct AttnLaunch {
@@ -112,13 +116,18 @@ struct AttnLaunch {
   int32_t max_blocks_per_seq;
   float sm_scale;
   void* workspace;  // device; holds the partial results at plan->off_partials
-  const void* plan_image;  // device-visible [WorkItem | MergeItem] image at the plan's offsets
+  const void* plan_image;  // device-visible [WorkItem | MergeItem | StageSeq] image at the plan's offsets
   const Plan* plan;
   void* stream;
-  void* ev_start;  // optional hipEvent_t pair recorded around the main kernel
-  void* ev_stop;
+  // optional hipEvent_t handles (measurement aid): [0], [1] start and stop of the main
+  // kernel's dispatch; [2] start of the call's first kernel when that is another one (the
+  // fp8 copy); [3] stop of its last kernel when that is another one (the merge)
+  void* ev[4];
 };
 
+// One-time set-up of the attention kernels on the current device (dynamic LDS limits);
+// call before the first launch_attn() there.
+int prepare_attn_kernels();
 int launch_attn(const AttnLaunch& a);
 int launch_kv_append(const cronus_kv_cache* cache, const void* k_src, const void* v_src,
                      const int32_t* cu_tokens, const int32_t* start_pos, const int32_t* block_tables,

@@ -45,7 +45,7 @@ Scratch& scratch() {
 }  // namespace
 
 int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const int32_t* chunk_lens,
-               int32_t n_seqs, int32_t max_blocks_per_seq, int n_cus, Plan* plan) {
+               int32_t n_seqs, int32_t max_blocks_per_seq, int n_cus, Plan* plan, bool allow_stage) {
   const int D = cache->head_dim, Hq = cache->num_q_heads, Hkv = cache->num_kv_heads;
   const int G = Hq / Hkv;
   const int group = std::min(G, kNarrowRows);          // q heads handled together by one item
@@ -140,7 +140,7 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
   constexpr int kStageMinTiles = 16, kStageMinTilesLong = 8, kStageLongKeys = 8192;
   constexpr long long kStageMaxBytes = 1LL << 30;  // of workspace for the copy; later sequences convert on the fly
   const long long stage_block_bytes = 2LL * Hkv * kBlock * D * 2;  // K and V of one block, bf16
-  const bool fp8 = cache->kv_dtype == CRONUS_KV_FP8_E4M3;
+  const bool fp8 = cache->kv_dtype == CRONUS_KV_FP8_E4M3 && allow_stage;  // candidates for the bf16 copy
   int32_t q_off = 0;
 
   auto add_narrow = [&](int s, int kvh, int head0, int nh, int q_tok0, int n_tok, int kv_total) {
@@ -267,8 +267,11 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
   // Given equal work, the odd-numbered XCDs of an MI355X finished later than the
   // even-numbered ones in every per-work-group trace taken: about 3 % on wide tiles
   // (MFMA-bound), about 6 % on decode spans (HBM-bound).  Work dealt to an odd XCD is
-  // therefore booked that much heavier.
-  constexpr double kOddXcdWide = 1.03, kOddXcdNarrow = 1.06;
+  // therefore booked that much heavier.  This, like the queue numbering itself, describes a
+  // device of 256 CUs in 8 XCDs whose dispatcher deals work-groups round-robin (MI355X in
+  // its single-partition mode); on any other CU count the queues are booked evenly.
+  const bool mi355x_spx = n_cus == 256;
+  const double kOddXcdWide = mi355x_spx ? 1.03 : 1.0, kOddXcdNarrow = mi355x_spx ? 1.06 : 1.0;
   auto least_loaded = [&]() {
     int x = 0;
     for (int i = 1; i < kXcds; ++i) if (load[i] < load[x]) x = i;
@@ -375,8 +378,8 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
   plan->n_stage_seqs = (int32_t)sc.stages.size();
   plan->n_stage_blocks = n_stage_blocks;
   plan->off_stage = align_up(plan->off_merge + sizeof(MergeItem) * sc.merges.size(), 256);
-  plan->upload_bytes = align_up(plan->off_stage + sizeof(StageSeq) * sc.stages.size(), 256);
-  plan->off_partials = plan->upload_bytes;
+  plan->image_bytes = align_up(plan->off_stage + sizeof(StageSeq) * sc.stages.size(), 256);
+  plan->off_partials = 0;
   plan->off_stage_k = align_up(plan->off_partials + sizeof(float) * partial_floats(D) * (size_t)n_partials, 256);
   const size_t stage_bytes = (size_t)n_stage_blocks * Hkv * kBlock * D * 2;  // bf16 copy of K (and of V)
   plan->off_stage_v = align_up(plan->off_stage_k + stage_bytes, 256);

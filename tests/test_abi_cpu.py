@@ -38,8 +38,11 @@ def test_workspace_and_plan_sizes_for_the_five_configs():
         st = B.cronus_attn_mixed_plan_stats(c, b.prefix_lens, b.chunk_lens)
         ws = B.cronus_attn_mixed_workspace_bytes(c, b.prefix_lens, b.chunk_lens)
         assert st["items"] >= sh.n_kv_heads * int((b.chunk_lens > 0).sum())
-        assert ws >= 16 * b.n_seqs + 48 * st["items"] + 4 * 32 * (sh.head_dim + 2) * st["partials"]
-        assert ws % 256 == 0
+        # the workspace holds the partial results (and, for fp8, the bf16 copy), not the work list
+        copy = 2 * st["copy_blocks"] * sh.n_kv_heads * 16 * sh.head_dim * 2
+        partials = 4 * 32 * (sh.head_dim + 2) * st["partials"]
+        assert partials + copy <= ws <= partials + copy + 1024 and ws % 256 == 0 and ws > 0
+        assert (st["merge_groups"] > 0) == (st["partials"] > 0)
 
 
 def test_argument_checks_without_a_device():
@@ -81,3 +84,48 @@ def test_workload_recipes():
     # bf16 helper: round to nearest even
     x = np.array([1.0, 1.00390625, 1.01171875, -2.5], dtype=np.float32)  # 1+2^-8 is a tie -> 1.0
     assert W.f32_to_bf16_bits(x).tolist() == [0x3F80, 0x3F80, 0x3F82, 0xC020]
+
+
+def test_error_paths_forced_from_the_host():
+    """Every error that the header promises 'before anything is launched' is returned with
+    made-up device addresses (nothing may touch them), and on a machine without a GPU a call
+    with valid arguments ends in CRONUS_ERR_HIP at the device set-up, again before a launch."""
+    fake = 0x7F0000001000  # never dereferenced: all of these calls return from the host-side checks
+    c = B.make_cache(fake, fake, 100, 8, 2, 64)
+    ok = dict(max_blocks_per_seq=4, sm_scale=0.125)
+    call = lambda cache, q, out, P, C, bt, ws, ws_bytes, **kw: B.cronus_attn_mixed(
+        cache, q, out, P, C, bt, kw.get("max_blocks_per_seq", 4), kw.get("sm_scale", 0.125), ws, ws_bytes, check=False)
+    need = B.cronus_attn_mixed_workspace_bytes(c, [40], [3])
+    assert need >= 256
+    assert call(c, fake, fake, [40], [3], fake, None, need) == B.CRONUS_ERR_WORKSPACE        # no workspace
+    assert call(c, fake, fake, [40], [3], fake, fake + 8, need) == B.CRONUS_ERR_WORKSPACE    # misaligned
+    assert call(c, fake, fake, [40], [3], fake, fake, need - 1) == B.CRONUS_ERR_WORKSPACE    # too small
+    assert call(c, fake, fake, [62], [3], fake, fake, need) == B.CRONUS_ERR_INVALID_ARG      # 65 keys > 4 blocks
+    assert call(c, fake, fake, [-1], [3], fake, fake, need) == B.CRONUS_ERR_INVALID_ARG
+    assert call(c, fake, fake, [40], [-3], fake, fake, need) == B.CRONUS_ERR_INVALID_ARG
+    assert call(c, None, fake, [40], [3], fake, fake, need) == B.CRONUS_ERR_INVALID_ARG      # q
+    assert call(c, fake, None, [40], [3], fake, fake, need) == B.CRONUS_ERR_INVALID_ARG      # out
+    assert call(c, fake, fake, [40], [3], None, fake, need) == B.CRONUS_ERR_INVALID_ARG      # block tables
+    for bad_scale in (0.0, -1.0, float("nan"), float("inf")):
+        assert call(c, fake, fake, [40], [3], fake, fake, need, sm_scale=bad_scale) == B.CRONUS_ERR_INVALID_ARG
+    assert call(c, fake, fake, [40], [3], fake, fake, need, max_blocks_per_seq=0) == B.CRONUS_ERR_INVALID_ARG
+    assert call(c, fake, fake, [40, 7], [0, 0], fake, None, 0) == B.CRONUS_OK                # nothing to do
+    for bad in (B.make_cache(fake, fake, 100, 8, 2, 96), B.make_cache(fake, fake, 100, 8, 2, 64, kv_dtype=7),
+                B.make_cache(fake, fake, 100, 8, 3, 64), B.make_cache(fake, fake, 100, 8, 2, 64, block_size=32)):
+        assert call(bad, fake, fake, [40], [3], fake, fake, need) == B.CRONUS_ERR_UNSUPPORTED
+    for bad in (B.make_cache(None, fake, 100, 8, 2, 64), B.make_cache(fake, fake, 0, 8, 2, 64),
+                B.make_cache(fake, fake, 100, 8, 2, 64, k_scale=fake, v_scale=fake),           # scales on a bf16 cache
+                B.make_cache(fake, fake, 100, 8, 2, 64, kv_dtype=B.CRONUS_KV_FP8_E4M3)):       # fp8 without scales
+        assert call(bad, fake, fake, [40], [3], fake, fake, need) == B.CRONUS_ERR_INVALID_ARG
+    # the scatter and the gather: counts and pointers
+    for fn in (B.cronus_kv_append, B.cronus_kv_gather):
+        assert fn(c, fake, fake, fake, fake, fake, 4, -1, 5, check=False) == B.CRONUS_ERR_INVALID_ARG
+        assert fn(c, fake, fake, fake, fake, fake, 4, 1, -5, check=False) == B.CRONUS_ERR_INVALID_ARG
+        assert fn(c, fake, fake, fake, fake, fake, 0, 1, 5, check=False) == B.CRONUS_ERR_INVALID_ARG
+        assert fn(c, fake, fake, None, fake, fake, 4, 1, 5, check=False) == B.CRONUS_ERR_INVALID_ARG
+        assert fn(c, fake, fake, fake, fake, fake, 4, 1, 0, check=False) == B.CRONUS_OK       # no rows: no-op
+    import torch
+    if not torch.cuda.is_available():
+        # valid arguments, no device: the set-up that precedes the first launch reports it
+        assert call(c, fake, fake, [40], [3], fake, fake, need) == B.CRONUS_ERR_HIP
+        assert B.cronus_kv_append(c, fake, fake, fake, fake, fake, 4, 1, 5, check=False) == B.CRONUS_ERR_HIP

@@ -23,6 +23,12 @@ def check_plan(shape, P, C):
     P, C = np.asarray(P), np.asarray(C)
     items, stats = plan_for(shape, P, C)
     assert len(items) == stats["items"]
+    verify_items(shape, P, C, items, stats)
+    return items, stats
+
+
+def verify_items(shape, P, C, items, stats):
+    """The invariants of a work list (whatever planner options or CU count produced it)."""
     G = shape.n_q_heads // shape.n_kv_heads
     real = items[items[:, F["wide"]] >= 0]
     assert (items[items[:, F["wide"]] < 0][:, :8] == 0).all()  # idle slots carry nothing
@@ -70,7 +76,6 @@ def check_plan(shape, P, C):
     for it in real[real[:, F["partial"]] >= 0]:
         slots += list(range(int(it[F["partial"]]), int(it[F["partial"]]) + (8 if it[F["wide"]] >= 1 else 1)))
     assert sorted(slots) == list(range(stats["partials"]))
-    return items, stats
 
 
 @pytest.mark.parametrize("cid", [1, 2, 3, 4])

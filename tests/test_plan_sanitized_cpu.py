@@ -1,0 +1,194 @@
+"""The planner (csrc/plan.cpp) and the balancer (csrc/balancer.cpp) under AddressSanitizer
+and UndefinedBehaviorSanitizer: a host-only build of the product's sources as they are,
+driven through tests/native/plan_check_main.cpp.  The planner runs inside every
+cronus_attn_mixed call, with vectors that are erased from, bucket sorts and thread-local
+scratch reused from call to call; here it plans seeded random batches over head shapes
+(including more than 32 q heads per KV head), CU counts (1, 64, 256, 304), both cache types,
+with and without the fp8 copy, ten thousand sequences in one batch, and lengths on both sides
+of every threshold of the planner.  Every plan must satisfy the coverage invariants of
+tests/test_plan_cpu.py, equal the shipped library's plan where the library can be asked
+(256 CUs), and the process must end without a sanitizer report."""
+import os
+import shutil
+import subprocess
+
+import numpy as np
+import pytest
+
+from oracle import cronus_oracle as orc
+from paper_2509_17357_amd import binding as B
+from paper_2509_17357_amd import workloads as W
+
+import test_plan_cpu as TP
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CSRC = os.path.join(ROOT, "paper_2509_17357_amd", "csrc")
+
+
+@pytest.fixture(scope="module")
+def exe(tmp_path_factory):
+    cxx = shutil.which("g++")
+    if cxx is None:
+        pytest.skip("no host C++ compiler")
+    out = str(tmp_path_factory.mktemp("plan_check") / "plan_check")
+    cmd = [cxx, "-std=c++17", "-O1", "-g", "-ffp-contract=off", "-fsanitize=address,undefined",
+           "-fno-sanitize-recover=all", "-Wno-unknown-pragmas", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+           os.path.join(ROOT, "tests", "native", "plan_check_main.cpp"), os.path.join(CSRC, "plan.cpp"),
+           os.path.join(CSRC, "balancer.cpp"), "-o", out]
+    subprocess.run(cmd, check=True)
+    return out
+
+
+def run_cases(exe, lines):
+    """All cases through ONE process (so the planner's thread-local scratch is reused from
+    batch to batch, as in a serving loop); returns the parsed replies in order."""
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    env.pop("LD_PRELOAD", None)  # the sanitizer runtime must come first in the library list
+    r = subprocess.run([exe], input="\n".join(lines) + "\n", capture_output=True, text=True, env=env)
+    assert r.returncode == 0, r.stderr[-3000:]
+    assert "ERROR" not in r.stderr and "runtime error" not in r.stderr, r.stderr[-3000:]
+    replies, cur = [], None
+    for ln in r.stdout.splitlines():
+        f = ln.split()
+        if f[0] == "plan":
+            cur = {"rc": int(f[1]), "stats": {"items": int(f[2]), "wide_items": int(f[3]), "partials": int(f[4]),
+                                               "merge_groups": int(f[5]), "merge_rows": int(f[6]),
+                                               "copy_blocks": int(f[7])},
+                   "total_bytes": int(f[8]), "image_bytes": int(f[9]), "items": [], "merges": []}
+            replies.append(cur)
+        elif f[0] == "i":
+            cur["items"].append([int(x) for x in f[1:]])
+        elif f[0] == "m":
+            cur["merges"].append([int(x) for x in f[1:]])
+        elif f[0] == "split":
+            replies.append({"rc": int(f[1]), "l_p": int(f[2]), "tp": float(f[3]), "tc": float(f[4])})
+    for rep in replies:
+        if "items" in rep:
+            rep["items"] = np.array(rep["items"], dtype=np.int32).reshape(-1, 12)
+    return replies
+
+
+def plan_line(shape, n_cus, allow_stage, P, C):
+    return "plan %d %d %d %d %d %d %d " % (shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.kv_dtype == "fp8",
+                                           n_cus, allow_stage, len(P)) + " ".join(f"{p} {c}" for p, c in zip(P, C))
+
+
+SHAPES = [W.HeadShape(32, 8, 128), W.HeadShape(28, 4, 128), W.HeadShape(8, 2, 64), W.HeadShape(64, 8, 128, "fp8"),
+          W.HeadShape(16, 16, 64), W.HeadShape(64, 1, 128), W.HeadShape(16, 2, 128, "fp8"), W.HeadShape(80, 2, 64),
+          W.HeadShape(40, 1, 128, "fp8")]
+
+
+def threshold_cases():
+    """Lengths on both sides of every constant of the planner."""
+    cases = []
+    for x in (-1, 0, 1):
+        cases += [
+            ([1024 + x - 512], [512]),           # longest tile = kMinPiece (16 K/V tiles) +- 1: half tiles or not
+            ([1536 + x - 512], [512]),           # 1.5 x kMinPiece: the half-tile limit, first key spans
+            ([3000], [64 * 15 + x]),             # fp8: 15 / 16 tiles around the bf16-copy threshold
+            ([8192 - 8 * 32 + x], [8 * 32]),     # fp8, G = 8: 8 tiles behind 8192 keys +- 1 (second copy threshold)
+            ([8192 - 7 * 32 + x], [7 * 32]),
+            ([500], [32 + x]),                   # 32 rows: the narrow / wide boundary at one head per row
+            ([500], [8 + x]),                    # 8 tokens x 4 heads = 32 rows
+            ([500], [4 + x]),                    # 4 tokens x 8 heads
+            ([0], [64 + x]), ([0], [256 + x]),   # one tile +- 1 token, four tiles +- 1
+            ([4096 * 3 + 1024 + x], [1]),        # a decode whose last span is a quarter span +- 1 (sliver rule)
+            ([511 + x], [1]), ([255 + x], [1]),  # span granularity
+            ([2 ** 20 + x], [1]),                # a million keys
+        ]
+    cases += [([0] * 32, [64 * 16] * 32), ([0] * 31, [64 * 16] * 31),   # 16 tiles per CU at 256 CUs: paired or not
+              ([200000, 200000, 100], [1024, 1024, 1024])]              # fp8 copy: the second sequence would pass the 1 GiB cap at Hkv = 8
+    return cases
+
+
+def test_planner_under_sanitizers_thresholds_and_cu_counts(exe):
+    lines, meta = [], []
+    for shape in SHAPES:
+        for P, C in threshold_cases():
+            for n_cus in (1, 64, 256, 304):
+                if n_cus != 256 and sum(C) > 4000:
+                    continue
+                for allow_stage in ((0, 1) if shape.kv_dtype == "fp8" else (1,)):
+                    lines.append(plan_line(shape, n_cus, allow_stage, P, C))
+                    meta.append((shape, n_cus, allow_stage, P, C))
+    replies = run_cases(exe, lines)
+    assert len(replies) == len(meta)
+    for (shape, n_cus, allow_stage, P, C), rep in zip(meta, replies):
+        assert rep["rc"] == 0
+        if not allow_stage:
+            assert rep["stats"]["copy_blocks"] == 0 and (rep["items"][:, TP.F["wide"]] <= 1).all()
+        cheap = sum(c * shape.n_q_heads for c in C) <= 40000   # the row-by-row cover check is Python-slow
+        if cheap:
+            TP.verify_items(shape, np.asarray(P), np.asarray(C), rep["items"], rep["stats"])
+        if n_cus == 256 and allow_stage:
+            lib_items, lib_stats = TP.plan_for(shape, P, C)
+            assert np.array_equal(lib_items, rep["items"])
+            assert {k: lib_stats[k] for k in rep["stats"]} == rep["stats"]
+            c = B.make_cache(0, 0, 1 << 30, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                             B.CRONUS_KV_FP8_E4M3 if shape.kv_dtype == "fp8" else B.CRONUS_KV_BF16)
+            assert B.cronus_attn_mixed_workspace_bytes(c, P, C) == rep["total_bytes"]
+
+
+def test_planner_under_sanitizers_random_batches(exe):
+    lines, meta = [], []
+    for seed in range(60):
+        rng = np.random.default_rng([seed, 0x5A11])
+        shape = SHAPES[seed % len(SHAPES)]
+        n = int(rng.integers(1, 14))
+        kind = rng.integers(0, 4, n)
+        C = np.where(kind == 0, 0, np.where(kind == 1, 1, np.where(kind == 2, rng.integers(2, 70, n), rng.integers(70, 700, n))))
+        P = np.where(rng.random(n) < 0.3, 0, rng.integers(0, 6000, n))
+        if seed % 3 == 0:
+            P[int(rng.integers(0, n))] = int(rng.integers(20000, 60000))
+        if C.sum() == 0:
+            C[0] = 1
+        n_cus = [1, 64, 256, 304][seed % 4]
+        allow_stage = int(seed % 5 != 0)
+        lines.append(plan_line(shape, n_cus, allow_stage, P.tolist(), C.tolist()))
+        meta.append((shape, P, C))
+    for (shape, P, C), rep in zip(meta, run_cases(exe, lines)):
+        assert rep["rc"] == 0
+        TP.verify_items(shape, P.astype(np.int64), C.astype(np.int64), rep["items"], rep["stats"])
+
+
+def test_planner_under_sanitizers_ten_thousand_sequences(exe):
+    rng = np.random.default_rng(10 ** 4)
+    n = 10 ** 4
+    C = np.where(rng.random(n) < 0.02, 0, 1)
+    C[rng.integers(0, n, 20)] = rng.integers(2, 200, 20)     # a few chunks among the decodes
+    P = rng.integers(0, 3000, n)
+    shape = W.HeadShape(16, 4, 64)
+    lines = [plan_line(shape, n_cus, 1, P.tolist(), C.tolist()) for n_cus in (256, 1, 304)]
+    lines.append(plan_line(shape, 256, 1, [5], [1]))          # and a tiny batch right after, on the same scratch
+    reps = run_cases(exe, lines)
+    for rep in reps[:3]:
+        assert rep["rc"] == 0 and rep["stats"]["items"] >= 4 * int((C > 0).sum())
+        TP.verify_items(shape, P.astype(np.int64), C.astype(np.int64), rep["items"], rep["stats"])
+    TP.verify_items(shape, np.array([5]), np.array([1]), reps[3]["items"], reps[3]["stats"])
+    lib_items, _ = TP.plan_for(shape, P, C)
+    assert np.array_equal(lib_items, reps[0]["items"])
+
+
+def test_planner_rejects_bad_lengths_under_sanitizers(exe):
+    sh = W.SHAPE_8B
+    reps = run_cases(exe, [plan_line(sh, 256, 1, [-1], [5]), plan_line(sh, 256, 1, [5], [-1]),
+                           plan_line(sh, 256, 1, [2 ** 31 - 10], [100]), plan_line(sh, 256, 1, [], [])])
+    assert [r["rc"] for r in reps] == [B.CRONUS_ERR_INVALID_ARG] * 3 + [0] and reps[3]["stats"]["items"] == 0
+
+
+def test_balancer_under_sanitizers_matches_oracle(exe):
+    rng = np.random.default_rng(424242)
+    cases, lines = [], []
+    for _ in range(400):
+        l_in, n_d = int(rng.integers(1, 80000)), int(rng.integers(0, 512))
+        l_ctxd, n_free = int(rng.integers(0, 3 * 10 ** 6)), int(rng.integers(0, 8000))
+        coef = [float(rng.uniform(1e-5, 1e-3)), float(rng.uniform(0, 0.05)), float(rng.uniform(1e-7, 1e-5)),
+                float(rng.uniform(1e-8, 1e-6)), float(rng.uniform(0.005, 0.05))]
+        cases.append((l_in, n_d, l_ctxd, n_free, coef))
+        lines.append("split %d %d %d %d %s 16 512 512" % (l_in, n_d, l_ctxd, n_free, " ".join(repr(x) for x in coef)))
+    lines.append("split 1000 512 5 100 1e-4 0 1e-6 1e-7 0.01 16 512 512")      # no prefill token left
+    lines.append("split 9007199254740993 1 5 100 1e-4 0 1e-6 1e-7 0.01 16 512 512")  # beyond exact doubles
+    reps = run_cases(exe, lines)
+    for (l_in, n_d, l_ctxd, n_free, coef), rep in zip(cases, reps):
+        assert rep["rc"] == 0 and rep["l_p"] == orc.balancer_split(l_in, n_d, l_ctxd, n_free, *coef)
+    assert reps[-2]["rc"] == B.CRONUS_ERR_INVALID_ARG and reps[-1]["rc"] == B.CRONUS_ERR_INVALID_ARG
