@@ -142,6 +142,32 @@ int cronus_attn_mixed(const cronus_kv_cache* cache, const void* q, void* out,
                       const int32_t* block_tables, int32_t max_blocks_per_seq, int32_t n_seqs,
                       float sm_scale, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * cronus_attn_mixed_static - cronus_attn_mixed for callers that cannot allocate: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * without the workspace, same kernels, same results; the call allocates no device or pinned
+ * memory and calls no allocating HIP routine.  The plan image and the partial results live in
+ * a static device array inside the library (64 MiB, CRONUS_STATIC_SCRATCH_BYTES; every GPU
+ * that the library runs on holds its own copy until the process ends); the work list reaches
+ * it as kernel arguments of small upload launches (about one per 48 work items) on
+ * `hip_stream`.  The first call on a device looks up that device's address of the array and
+ * sets the kernels' attributes (no allocation either).
+ *   - CRONUS_ERR_WORKSPACE, nothing enqueued: the batch's plan image plus partial results
+ *     exceed the array (about 4000 partial slots at head_dim 128; every benchmark batch fits).
+ *   - fp8 cache: no bf16 copy is made (it would not fit); chunks of many tiles convert codes on
+ *     the fly, so results can differ from cronus_attn_mixed's in the last bf16 bit.
+ *   - Every call on a GPU uses that GPU's one array, which keeps the previous call's contents
+ *     (nothing in it has to start at zero: a call reads only what it has written).  Calls on
+ *     the same stream are ordered; calls that can overlap on one GPU (different streams or
+ *     threads without ordering) race on it and must not be made.
+ * Errors otherwise as cronus_attn_mixed.
+ */
+#define CRONUS_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+int cronus_attn_mixed_static(const cronus_kv_cache* cache, const void* q, void* out,
+                             const int32_t* prefix_lens, const int32_t* chunk_lens,
+                             const int32_t* block_tables, int32_t max_blocks_per_seq,
+                             int32_t n_seqs, float sm_scale, void* hip_stream);
+
 /* Bytes of workspace cronus_attn_mixed needs for these lengths (host arrays); 0 on
  * invalid arguments.  Depends only on the shapes and lengths, not on cache contents. */
 size_t cronus_attn_mixed_workspace_bytes(const cronus_kv_cache* cache, const int32_t* prefix_lens,

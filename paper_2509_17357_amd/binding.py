@@ -23,7 +23,8 @@ CRONUS_ERR_HIP = 4
 CRONUS_KV_BF16 = 0
 CRONUS_KV_FP8_E4M3 = 1
 
-EXPORTS = ("cronus_kv_append", "cronus_kv_gather", "cronus_attn_mixed", "cronus_attn_mixed_workspace_bytes",
+EXPORTS = ("cronus_kv_append", "cronus_kv_gather", "cronus_attn_mixed", "cronus_attn_mixed_static",
+           "cronus_attn_mixed_workspace_bytes",
            "cronus_attn_mixed_plan_stats", "cronus_attn_mixed_plan_items", "cronus_balancer_split",
            "cronus_profile_events", "cronus_status_string", "cronus_version")
 
@@ -72,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.cronus_balancer_split.restype = ctypes.c_int
         L.cronus_attn_mixed.argtypes = [cp, vp, vp, i32p, i32p, vp, i32, i32, ctypes.c_float, vp, ctypes.c_size_t, vp]
         L.cronus_attn_mixed.restype = ctypes.c_int
+        L.cronus_attn_mixed_static.argtypes = [cp, vp, vp, i32p, i32p, vp, i32, i32, ctypes.c_float, vp]
+        L.cronus_attn_mixed_static.restype = ctypes.c_int
         L.cronus_attn_mixed_workspace_bytes.argtypes = [cp, i32p, i32p, i32]
         L.cronus_attn_mixed_workspace_bytes.restype = ctypes.c_size_t
         L.cronus_attn_mixed_plan_stats.argtypes = [cp, i32p, i32p, i32, ctypes.POINTER(ctypes.c_int64)]
@@ -238,4 +241,19 @@ def cronus_attn_mixed(cache: cronus_kv_cache, q, out, prefix_lens, chunk_lens, b
                                  ctypes.c_size_t(int(workspace_bytes)), ctypes.c_void_p(stream))
     if check and rc != CRONUS_OK:
         raise CronusError(rc, "cronus_attn_mixed")
+    return rc
+
+
+def cronus_attn_mixed_static(cache: cronus_kv_cache, q, out, prefix_lens, chunk_lens, block_tables,
+                             max_blocks_per_seq: int, sm_scale: float, stream: int = 0, check=True) -> int:
+    """cronus_attn_mixed without a workspace (the library's static device scratch is used)."""
+    p, pp = _host_i32(prefix_lens)
+    c, cp = _host_i32(chunk_lens)
+    if p.size != c.size:
+        raise ValueError("prefix_lens and chunk_lens differ in length")
+    rc = lib().cronus_attn_mixed_static(ctypes.byref(cache), _ptr(q), _ptr(out), pp, cp, _ptr(block_tables),
+                                        int(max_blocks_per_seq), int(p.size), ctypes.c_float(sm_scale),
+                                        ctypes.c_void_p(stream))
+    if check and rc != CRONUS_OK:
+        raise CronusError(rc, "cronus_attn_mixed_static")
     return rc

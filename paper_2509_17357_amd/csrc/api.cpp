@@ -42,6 +42,7 @@ int check_shape(const cronus_kv_cache* c) {
 struct DeviceState {
   int n_cus = 0;           // 0: not queried yet
   bool kernels_ready = false;
+  void* static_scratch = nullptr;  // this device's address of the library's static scratch array
 };
 constexpr int kMaxDevices = 64;
 DeviceState g_dev[kMaxDevices];
@@ -72,6 +73,7 @@ int prepare_device_locked(int* device) {
   *device = dev;
   if (!g_dev[dev].kernels_ready) {
     if (int rc = prepare_attn_kernels()) return rc;
+    if (int rc = static_scratch_resolve(&g_dev[dev].static_scratch)) return rc;
     g_dev[dev].kernels_ready = true;
   }
   return CRONUS_OK;
@@ -193,21 +195,38 @@ int64_t cronus_attn_mixed_plan_items(const cronus_kv_cache* cache, const int32_t
   return plan.n_items;
 }
 
-int cronus_attn_mixed(const cronus_kv_cache* cache, const void* q, void* out, const int32_t* prefix_lens,
-                      const int32_t* chunk_lens, const int32_t* block_tables, int32_t max_blocks_per_seq,
-                      int32_t n_seqs, float sm_scale, void* workspace, size_t workspace_bytes, void* hip_stream) {
+namespace {
+
+// Host-side checks shared by the two attention entry points; *total_q = sum of chunk_lens.
+int check_attn_args(const cronus_kv_cache* cache, const void* q, const void* out, const int32_t* prefix_lens,
+                    const int32_t* chunk_lens, const int32_t* block_tables, int32_t max_blocks_per_seq,
+                    int32_t n_seqs, float sm_scale, long long* total_q) {
+  *total_q = 0;
   if (int rc = check_cache(cache)) return rc;
   if (n_seqs < 0 || max_blocks_per_seq <= 0) return CRONUS_ERR_INVALID_ARG;
   if (!(sm_scale > 0.f) || !std::isfinite(sm_scale)) return CRONUS_ERR_INVALID_ARG;
   if (n_seqs == 0) return CRONUS_OK;
   if (!prefix_lens || !chunk_lens || !block_tables) return CRONUS_ERR_INVALID_ARG;
-  long long total_q = 0;
+  long long total = 0;
   for (int s = 0; s < n_seqs; ++s) {
     if (chunk_lens[s] < 0 || prefix_lens[s] < 0) return CRONUS_ERR_INVALID_ARG;
-    total_q += chunk_lens[s];
+    total += chunk_lens[s];
   }
+  if (total > 0 && (total > 0x7fffffffLL || !q || !out)) return CRONUS_ERR_INVALID_ARG;
+  *total_q = total;
+  return CRONUS_OK;
+}
+
+}  // namespace
+
+int cronus_attn_mixed(const cronus_kv_cache* cache, const void* q, void* out, const int32_t* prefix_lens,
+                      const int32_t* chunk_lens, const int32_t* block_tables, int32_t max_blocks_per_seq,
+                      int32_t n_seqs, float sm_scale, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  long long total_q = 0;
+  if (int rc = check_attn_args(cache, q, out, prefix_lens, chunk_lens, block_tables, max_blocks_per_seq, n_seqs,
+                               sm_scale, &total_q))
+    return rc;
   if (total_q == 0) return CRONUS_OK;
-  if (total_q > 0x7fffffffLL || !q || !out) return CRONUS_ERR_INVALID_ARG;
 
   Plan plan;
   const int n_cus = device_cus();
@@ -233,6 +252,39 @@ int cronus_attn_mixed(const cronus_kv_cache* cache, const void* q, void* out, co
   return rc;
 }
 
+int cronus_attn_mixed_static(const cronus_kv_cache* cache, const void* q, void* out, const int32_t* prefix_lens,
+                             const int32_t* chunk_lens, const int32_t* block_tables, int32_t max_blocks_per_seq,
+                             int32_t n_seqs, float sm_scale, void* hip_stream) {
+  long long total_q = 0;
+  if (int rc = check_attn_args(cache, q, out, prefix_lens, chunk_lens, block_tables, max_blocks_per_seq, n_seqs,
+                               sm_scale, &total_q))
+    return rc;
+  if (total_q == 0) return CRONUS_OK;
+
+  // no bf16 copy of fp8 sequences here: it can take a gigabyte; their chunk tiles convert on the fly
+  Plan plan;
+  if (int rc = build_plan(cache, prefix_lens, chunk_lens, n_seqs, max_blocks_per_seq, device_cus(), &plan, false))
+    return rc;
+  if (plan.n_items > 0x7fffffffLL) return CRONUS_ERR_INVALID_ARG;
+  // scratch layout: [plan image | partial results]; both sizes are multiples of 256
+  if (plan.image_bytes > kStaticScratchBytes || plan.total_bytes > kStaticScratchBytes - plan.image_bytes)
+    return CRONUS_ERR_WORKSPACE;
+
+  std::lock_guard<std::mutex> lock(g_mu);
+  int dev = 0;
+  if (int rc = prepare_device_locked(&dev)) return rc;  // first call on a device: looks up its scratch address
+  unsigned char* base = static_cast<unsigned char*>(g_dev[dev].static_scratch);
+  static thread_local std::vector<unsigned char> image;  // host memory; grows to the largest plan seen
+  image.resize(plan.image_bytes);
+  write_plan(&plan, image.data());
+  if (int rc = static_scratch_upload(base, image.data(), plan.image_bytes, hip_stream)) return rc;
+  // Nothing in the scratch has to start at zero: the kernels read the plan image that was just
+  // stored and, of the partial slots, exactly the rows that items of this call write first.
+  AttnLaunch a{cache, q, out, block_tables, max_blocks_per_seq, sm_scale, base + plan.image_bytes, base, &plan,
+               hip_stream, {g_ev[0], g_ev[1], g_ev[2], g_ev[3]}};
+  return launch_attn(a);
+}
+
 void cronus_profile_events(void* main_start, void* main_stop, void* first_start, void* last_stop) {
   std::lock_guard<std::mutex> lock(g_mu);
   g_ev[0] = main_start;
@@ -252,6 +304,6 @@ const char* cronus_status_string(int status) {
   }
 }
 
-int cronus_version(void) { return 300; }  // 0.3.0: cronus_profile_events takes four events, plan_stats six numbers
+int cronus_version(void) { return 400; }  // 0.4.0: + cronus_attn_mixed_static
 
 }  // extern "C"

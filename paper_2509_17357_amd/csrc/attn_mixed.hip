@@ -31,9 +31,17 @@
 #include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 
+#include <cstring>
 #include <type_traits>
 
 #include "cronus_internal.h"
+
+// Scratch of cronus_attn_mixed_static (the entry point for callers that cannot allocate): the
+// plan image and the partial results of one call.  Each GPU that loads the library holds its
+// own copy of this array at its own address until the process ends.  In host code the name
+// is only a handle for hipGetSymbolAddress: static_scratch_resolve() below turns it into the
+// device address, and every kernel argument is derived from that address, never from the name.
+static __device__ __align__(256) unsigned char scratch[cronus::kStaticScratchBytes];
 
 namespace cronus {
 namespace {
@@ -1210,7 +1218,44 @@ int launch_typed(const AttnLaunch& a, const AttnParams& p) {
   return CRONUS_OK;
 }
 
+// Plan upload of the no-allocation variant: the bytes travel as kernel arguments (copied by
+// the runtime at launch, so neither a pinned staging buffer nor a host-to-device copy is
+// needed), one work-group stores them.
+constexpr int kUploadVecs = 192;  // 3 KiB of payload per launch, inside the 4 KiB argument limit
+struct UploadChunk {
+  u32x4 v[kUploadVecs];
+};
+__global__ __launch_bounds__(256) void plan_upload_kernel(UploadChunk c, u32x4* dst, int n_vec) {
+  const int i = threadIdx.x;
+  if (i < n_vec) dst[i] = c.v[i];
+}
+
 }  // namespace
+
+int static_scratch_resolve(void** device_ptr) {
+  void* ptr = nullptr;
+  if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+    (void)hipGetLastError();
+    return CRONUS_ERR_HIP;
+  }
+  *device_ptr = ptr;
+  return CRONUS_OK;
+}
+
+int static_scratch_upload(void* dst, const void* host_src, size_t bytes, void* stream) {
+  // dst is 256-byte aligned and bytes a multiple of 16 (the plan image is padded to 256)
+  const unsigned char* src = static_cast<const unsigned char*>(host_src);
+  unsigned char* out = static_cast<unsigned char*>(dst);
+  for (size_t off = 0; off < bytes; off += sizeof(UploadChunk)) {
+    const size_t n = bytes - off < sizeof(UploadChunk) ? bytes - off : sizeof(UploadChunk);
+    UploadChunk c;
+    memcpy(&c, src + off, n);
+    hipLaunchKernelGGL(plan_upload_kernel, dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream), c,
+                       reinterpret_cast<u32x4*>(out + off), (int)((n + 15) / 16));
+    if (hipGetLastError() != hipSuccess) return CRONUS_ERR_HIP;
+  }
+  return CRONUS_OK;
+}
 
 int wide_rows_for(int /*head_dim*/, int /*kv_dtype*/) { return kWaves * 32; }
 

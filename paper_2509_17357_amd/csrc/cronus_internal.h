@@ -129,6 +129,15 @@ struct AttnLaunch {
 // call before the first launch_attn() there.
 int prepare_attn_kernels();
 int launch_attn(const AttnLaunch& a);
+
+// The no-allocation variant's device memory: a static array in the library's device image
+// (attn_mixed.hip).  static_scratch_resolve() looks up its address on the current device
+// (once per device, at set-up); static_scratch_upload() enqueues the copy of `bytes` bytes of
+// host data to `dst` inside it as kernel arguments (no staging buffer, nothing allocated; the
+// host data may be reused as soon as the call returns).
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+int static_scratch_resolve(void** device_ptr);
+int static_scratch_upload(void* dst, const void* host_src, size_t bytes, void* stream);
 int launch_kv_append(const cronus_kv_cache* cache, const void* k_src, const void* v_src,
                      const int32_t* cu_tokens, const int32_t* start_pos, const int32_t* block_tables,
                      int32_t max_blocks_per_seq, int32_t n_seqs, int32_t n_tokens, void* stream);
