@@ -133,7 +133,10 @@ int cronus_kv_append(const cronus_kv_cache* cache, const void* k_src, const void
  *                  must not be shared by calls that can overlap on the device
  * The work list is built on the host during the call and read by the kernels from
  * pinned, device-mapped host memory that the library owns (a ring of 8 buffers, grown on
- * demand, never freed; the ninth call in flight waits on the host for the first).
+ * demand, never freed; the ninth call in flight waits on the host for the first).  The main
+ * kernel's work-groups stay resident and take their items from work queues whose heads (a
+ * few integers per call in flight) live in a small static device array of the library; every
+ * launch leaves its set of heads zero for the next one.
  * Errors: INVALID_ARG (null pointers, negative lengths, prefix+chunk >
  * 16*max_blocks_per_seq), UNSUPPORTED, WORKSPACE, HIP.
  */
@@ -186,17 +189,19 @@ int cronus_attn_mixed_plan_stats(const cronus_kv_cache* cache, const int32_t* pr
 
 /*
  * cronus_attn_mixed_plan_items - the work list itself, for inspection and tests (host
- * only, nothing is launched).  Writes up to `capacity` items, 12 int32 each, in grid
- * order: seq, kv_head, head0, n_heads, q_tok0, n_tok, kv_begin, kv_end, partial, wide,
- * pair_tok1, pair_ntok.  wide >= 1: chunk tile over keys [kv_begin, kv_end) (wide >= 2,
- * fp8 cache only: it reads the launch's bf16 copy of its sequence, whose first block
- * there is wide - 2); wide = 0:
- * narrow item over keys [kv_begin, kv_end); partial >= 0 when the item's result is merged
- * with other spans of the same rows; wide = -1: idle slot.  pair_tok1 > 0 (wide items of
- * launches with many tiles per CU): the same work-group then also computes the earlier
- * tile of pair_ntok tokens that starts at chunk token pair_tok1 - 1, against all keys up
- * to that tile's causal end.  Returns the number of items of the plan (which may exceed capacity), or
- * a negative cronus_status on invalid arguments.  items may be NULL when capacity = 0.
+ * only, nothing is launched).  Writes up to `capacity` items, 13 int32 each: seq, kv_head,
+ * head0, n_heads, q_tok0, n_tok, kv_begin, kv_end, partial, wide, pair_tok1, pair_ntok,
+ * queue.  The items form 8 queues, listed one after the other, each in the order in which
+ * its items are taken: the main kernel's work-groups stay resident (one per CU) and take
+ * items from the queue of the XCD they run on, then from the other queues.  wide >= 1: chunk
+ * tile over keys [kv_begin, kv_end) (wide >= 2, fp8 cache only: it reads the launch's bf16
+ * copy of its sequence, whose first block there is wide - 2); wide = 0: narrow item over
+ * keys [kv_begin, kv_end); partial >= 0 when the item's result is merged with other spans
+ * of the same rows.  pair_tok1 > 0 (wide items of launches with many tiles per CU): the same
+ * work-group then also computes the earlier tile of pair_ntok tokens that starts at chunk
+ * token pair_tok1 - 1, against all keys up to that tile's causal end.  Returns the number
+ * of items of the plan (which may exceed capacity), or a negative cronus_status on invalid
+ * arguments.  items may be NULL when capacity = 0.
  */
 int64_t cronus_attn_mixed_plan_items(const cronus_kv_cache* cache, const int32_t* prefix_lens,
                                      const int32_t* chunk_lens, int32_t n_seqs, int32_t* items,

@@ -43,6 +43,7 @@ struct DeviceState {
   int n_cus = 0;           // 0: not queried yet
   bool kernels_ready = false;
   void* static_scratch = nullptr;  // this device's address of the library's static scratch array
+  int* queue_sets = nullptr;       // and of its sets of queue heads
 };
 constexpr int kMaxDevices = 64;
 DeviceState g_dev[kMaxDevices];
@@ -74,6 +75,7 @@ int prepare_device_locked(int* device) {
   if (!g_dev[dev].kernels_ready) {
     if (int rc = prepare_attn_kernels()) return rc;
     if (int rc = static_scratch_resolve(&g_dev[dev].static_scratch)) return rc;
+    if (int rc = queue_sets_resolve(&g_dev[dev].queue_sets)) return rc;
     g_dev[dev].kernels_ready = true;
   }
   return CRONUS_OK;
@@ -94,6 +96,7 @@ struct Slot {
 void* g_ev[4] = {nullptr, nullptr, nullptr, nullptr};
 
 constexpr int kSlots = 8;
+static_assert(kQueueSets == kSlots + 1, "one set of queue heads per plan buffer, one for the static entry point");
 Slot g_slots[kMaxDevices][kSlots];  // a ring per device: the events that guard reuse belong to a device
 int g_next[kMaxDevices] = {0};
 
@@ -186,11 +189,13 @@ int64_t cronus_attn_mixed_plan_items(const cronus_kv_cache* cache, const int32_t
   write_plan(&plan, buf.data());
   const int64_t n = std::min<int64_t>(capacity, plan.n_items);
   const WorkItem* wi = reinterpret_cast<const WorkItem*>(buf.data() + plan.off_items);
+  int queue = 0;
   for (int64_t i = 0; i < n; ++i) {
+    while (queue + 1 < kQueues && i >= plan.q_base[queue] + plan.q_len[queue]) ++queue;
     const WorkItem& w = wi[i];
-    const int32_t row[12] = {w.seq, w.kv_head, w.head0, w.n_heads, w.q_tok0, w.n_tok, w.kv_begin, w.kv_end,
-                             w.partial, w.wide, w.pair_tok1, w.pair_ntok};
-    std::memcpy(items + 12 * i, row, sizeof(row));
+    const int32_t row[13] = {w.seq, w.kv_head, w.head0, w.n_heads, w.q_tok0, w.n_tok, w.kv_begin, w.kv_end,
+                             w.partial, w.wide, w.pair_tok1, w.pair_ntok, queue};
+    std::memcpy(items + 13 * i, row, sizeof(row));
   }
   return plan.n_items;
 }
@@ -243,8 +248,10 @@ int cronus_attn_mixed(const cronus_kv_cache* cache, const void* q, void* out, co
   Slot* slot = acquire_slot(dev, plan.image_bytes);
   if (!slot) return CRONUS_ERR_HIP;
   write_plan(&plan, slot->host);
+  // the set of queue heads that belongs to this plan buffer: free again when the buffer is
+  const int set = (int)(slot - g_slots[dev]);
   AttnLaunch a{cache, q, out, block_tables, max_blocks_per_seq, sm_scale, workspace, slot->dev, &plan, hip_stream,
-               {g_ev[0], g_ev[1], g_ev[2], g_ev[3]}};
+               g_dev[dev].queue_sets + set * kQueueSetInts, {g_ev[0], g_ev[1], g_ev[2], g_ev[3]}};
   const int rc = launch_attn(a);
   // whatever was launched may still read the slot
   if (hipEventRecord(slot->done, stream) != hipSuccess) return CRONUS_ERR_HIP;
@@ -280,8 +287,10 @@ int cronus_attn_mixed_static(const cronus_kv_cache* cache, const void* q, void* 
   if (int rc = static_scratch_upload(base, image.data(), plan.image_bytes, hip_stream)) return rc;
   // Nothing in the scratch has to start at zero: the kernels read the plan image that was just
   // stored and, of the partial slots, exactly the rows that items of this call write first.
+  // (The heads of the work queues, which must, live in their own small array, and every
+  // launch leaves them zero.)
   AttnLaunch a{cache, q, out, block_tables, max_blocks_per_seq, sm_scale, base + plan.image_bytes, base, &plan,
-               hip_stream, {g_ev[0], g_ev[1], g_ev[2], g_ev[3]}};
+               hip_stream, g_dev[dev].queue_sets + kSlots * kQueueSetInts, {g_ev[0], g_ev[1], g_ev[2], g_ev[3]}};
   return launch_attn(a);
 }
 
@@ -304,6 +313,6 @@ const char* cronus_status_string(int status) {
   }
 }
 
-int cronus_version(void) { return 400; }  // 0.4.0: + cronus_attn_mixed_static
+int cronus_version(void) { return 500; }  // 0.5.0: resident work-groups with work queues; plan items carry their queue
 
 }  // extern "C"

@@ -43,6 +43,12 @@
 // device address, and every kernel argument is derived from that address, never from the name.
 static __device__ __align__(256) unsigned char scratch[cronus::kStaticScratchBytes];
 
+// Heads of the work queues of the main kernel, kQueueSets sets (one per call that can be in
+// flight on a device: the plan buffers of the ring, and the static entry point's).  Zero when
+// the library's code object is loaded; the last work-group of a launch to finish puts its set
+// back to zero, so that no launch has to be preceded by a reset.
+static __device__ __align__(256) int queue_sets[cronus::kQueueSets * cronus::kQueueSetInts];
+
 namespace cronus {
 namespace {
 
@@ -76,6 +82,10 @@ struct AttnParams {
   int n_q_heads;
   int n_kv_heads;
   float scale_log2e;  // sm_scale * log2(e)
+  int* q_heads;       // head of queue x at q_heads[x * kCounterStride], finished work-groups at
+                      // q_heads[kQueues * kCounterStride]; all zero when the kernel starts and when it ends
+  int q_base[kQueues];
+  int q_len[kQueues];
 };
 
 // S^T row r of a 32-row MFMA tile holds key perm32(r) of the 32-key sub-tile
@@ -1067,30 +1077,95 @@ __device__ __forceinline__ void run_narrow(const AttnParams& p, const WorkItem& 
 }
 
 template <int D, bool FP8>
+constexpr int attn_lds_bytes() {
+  constexpr int wide_lds = 4 * 2 * 4 * 16 * D * 2;  // stages x (K + V tile of 64 keys)
+  constexpr int narrow_lds = kWaves * (2 * (D / 16) * 1024 + (FP8 ? 512 : 0)) + kWaves * 2 * 64 * 4;
+  constexpr int lds = wide_lds > narrow_lds ? wide_lds : narrow_lds;
+  static_assert(lds + 64 <= 160 * 1024, "LDS budget (the buffers and the 64-byte mailbox of the item loop)");
+  return lds;
+}
+
+// Index of the next work item for a work-group that runs on XCD `xcc`, or -1 when every
+// queue is empty: the own queue first, then the others in ring order (a queue's head only
+// grows, so a queue found empty stays empty).
+__device__ __forceinline__ int take_item(const AttnParams& p, int xcc) {
+  for (int k = 0; k < kQueues; ++k) {
+    const int y = (xcc + k) & (kQueues - 1);
+    if (p.q_len[y] == 0) continue;
+    const int idx = __hip_atomic_fetch_add(p.q_heads + y * kCounterStride, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (idx < p.q_len[y]) return p.q_base[y] + idx;
+  }
+  return -1;
+}
+
+// The work-groups of a launch stay resident, one per CU (the LDS they use allows no second
+// one), and work through the queues: the hardware dispatcher hands out work-groups strictly
+// in index order and stalls on the first XCD without a free CU, which couples the per-XCD
+// orders of a plain one-item-per-work-group launch; a resident work-group asks for its next
+// item when it is done with the last, whichever XCD's queue still has one.
+template <int D, bool FP8>
 __global__ __launch_bounds__(kThreads) void attn_mixed_kernel(AttnParams p) {
   extern __shared__ __align__(16) unsigned char smem[];
-  const WorkItem it = p.items[blockIdx.x];
-  if (it.wide < 0 || it.n_tok <= 0 || it.n_heads <= 0) return;  // idle slot that keeps the XCD queues aligned
-  if (it.wide) {
-    // the tile itself, then the earlier tile paired with it (if any): keys from 0, final output
-    WorkItem cur = it;
-    for (int rep = 0;; ++rep) {
-      if constexpr (FP8) {
-        if (cur.wide >= 2) run_wide_dma<D, true>(p, cur, smem);
-        else run_wide_staged<D, FP8, 1>(p, cur, smem);
-      } else {
-        run_wide_dma<D, false>(p, cur, smem);
+  static_assert(kQueues == 8, "XCC_ID is masked to three bits");
+  // hardware register XCC_ID (id 20), bits 3:0: the XCD this work-group runs on
+  const int xcc = __builtin_amdgcn_s_getreg(20 | (0 << 6) | ((4 - 1) << 11)) & (kQueues - 1);
+  int* const mailbox = reinterpret_cast<int*>(smem + attn_lds_bytes<D, FP8>());  // 16 ints behind the kernels' buffers
+  for (;;) {
+    // wave 0 takes the next item and posts its record; lanes 0-15 fetch one dword each
+    if (threadIdx.x < 64) {
+      int idx = 0;
+      if (threadIdx.x == 0) idx = take_item(p, xcc);
+      idx = __builtin_amdgcn_readfirstlane(idx);
+      if (threadIdx.x < 16) {
+        int v = threadIdx.x == 9 ? -1 : 0;  // field 9 = WorkItem::wide; -1: nothing left
+        if (idx >= 0) v = reinterpret_cast<const int*>(p.items + idx)[threadIdx.x];
+        mailbox[threadIdx.x] = v;
       }
-      if (rep || it.pair_tok1 <= 0) break;
-      cur.q_tok0 = it.pair_tok1 - 1;
-      cur.n_tok = it.pair_ntok;
-      cur.kv_begin = 0;
-      cur.kv_end = it.prefix_len + cur.q_tok0 + cur.n_tok;
-      cur.partial = -1;
-      __syncthreads();  // every wave is done with the first tile's LDS stages
     }
-  } else {
-    run_narrow<D, FP8>(p, it, smem);
+    __syncthreads();
+    WorkItem it;
+    {
+      int* f = reinterpret_cast<int*>(&it);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) f[i] = __builtin_amdgcn_readfirstlane(mailbox[i]);
+    }
+    __syncthreads();  // the mailbox may be rewritten, and the item's LDS buffers reused, from here on
+    if (it.wide < 0) break;
+    if (it.n_tok <= 0 || it.n_heads <= 0) continue;
+    if (it.wide) {
+      // the tile itself, then the earlier tile paired with it (if any): keys from 0, final output
+      WorkItem cur = it;
+      for (int rep = 0;; ++rep) {
+        if constexpr (FP8) {
+          if (cur.wide >= 2) run_wide_dma<D, true>(p, cur, smem);
+          else run_wide_staged<D, FP8, 1>(p, cur, smem);
+        } else {
+          run_wide_dma<D, false>(p, cur, smem);
+        }
+        if (rep || it.pair_tok1 <= 0) break;
+        cur.q_tok0 = it.pair_tok1 - 1;
+        cur.n_tok = it.pair_ntok;
+        cur.kv_begin = 0;
+        cur.kv_end = it.prefix_len + cur.q_tok0 + cur.n_tok;
+        cur.partial = -1;
+        __syncthreads();  // every wave is done with the first tile's LDS stages
+      }
+    } else {
+      run_narrow<D, FP8>(p, it, smem);
+    }
+    __syncthreads();  // every wave is done with this item's LDS before the next one's fetches land
+  }
+  // No queue has an item left for this work-group.  The last work-group of the launch to get
+  // here (every other one has taken its last ticket) zeroes the heads for the next launch.
+  if (threadIdx.x == 0) {
+    int* const done = p.q_heads + kQueues * kCounterStride;
+    const unsigned finished = __hip_atomic_fetch_add(done, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    if (finished == gridDim.x - 1) {
+#pragma unroll
+      for (int x = 0; x < kQueues; ++x)
+        __hip_atomic_store(p.q_heads + x * kCounterStride, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(done, 0, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    }
   }
 }
 
@@ -1163,19 +1238,10 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(AttnParams p)
 }
 
 template <int D, bool FP8>
-constexpr int attn_lds_bytes() {
-  constexpr int wide_lds = 4 * 2 * 4 * 16 * D * 2;  // stages x (K + V tile of 64 keys)
-  constexpr int narrow_lds = kWaves * (2 * (D / 16) * 1024 + (FP8 ? 512 : 0)) + kWaves * 2 * 64 * 4;
-  constexpr int lds = wide_lds > narrow_lds ? wide_lds : narrow_lds;
-  static_assert(lds <= 160 * 1024, "LDS budget");
-  return lds;
-}
-
-template <int D, bool FP8>
 int prepare_typed() {
   auto kern = attn_mixed_kernel<D, FP8>;
   return hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                             attn_lds_bytes<D, FP8>()) == hipSuccess ? CRONUS_OK : CRONUS_ERR_HIP;
+                             attn_lds_bytes<D, FP8>() + 64) == hipSuccess ? CRONUS_OK : CRONUS_ERR_HIP;
 }
 
 // Launches of one call, in order: the fp8 copy (if any sequence has one), the main kernel, the
@@ -1184,7 +1250,7 @@ int prepare_typed() {
 // differences are kernel durations without the launch latency around them.
 template <int D, bool FP8>
 int launch_typed(const AttnLaunch& a, const AttnParams& p) {
-  constexpr int lds = attn_lds_bytes<D, FP8>();
+  constexpr int lds = attn_lds_bytes<D, FP8>() + 64;
   hipStream_t s = static_cast<hipStream_t>(a.stream);
   const Plan& pl = *a.plan;
   auto ev = [&](int i) { return static_cast<hipEvent_t>(a.ev[i]); };
@@ -1202,9 +1268,9 @@ int launch_typed(const AttnLaunch& a, const AttnParams& p) {
   if (pl.n_items > 0) {
     auto kern = attn_mixed_kernel<D, FP8>;
     if (timed)
-      hipExtLaunchKernelGGL(kern, dim3((unsigned)pl.n_items), dim3(kThreads), lds, s, ev(0), ev(1), 0, p);
+      hipExtLaunchKernelGGL(kern, dim3((unsigned)pl.n_workgroups), dim3(kThreads), lds, s, ev(0), ev(1), 0, p);
     else
-      hipLaunchKernelGGL(kern, dim3((unsigned)pl.n_items), dim3(kThreads), lds, s, p);
+      hipLaunchKernelGGL(kern, dim3((unsigned)pl.n_workgroups), dim3(kThreads), lds, s, p);
     if (hipGetLastError() != hipSuccess) return CRONUS_ERR_HIP;
   }
   if (pl.n_merge > 0) {
@@ -1239,6 +1305,16 @@ int static_scratch_resolve(void** device_ptr) {
     return CRONUS_ERR_HIP;
   }
   *device_ptr = ptr;
+  return CRONUS_OK;
+}
+
+int queue_sets_resolve(int** device_ptr) {
+  void* ptr = nullptr;
+  if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(queue_sets)) != hipSuccess || ptr == nullptr) {
+    (void)hipGetLastError();
+    return CRONUS_ERR_HIP;
+  }
+  *device_ptr = static_cast<int*>(ptr);
   return CRONUS_OK;
 }
 
@@ -1282,6 +1358,11 @@ int launch_attn(const AttnLaunch& a) {
   p.items = reinterpret_cast<const WorkItem*>(image + pl.off_items);
   p.merges = reinterpret_cast<const MergeItem*>(image + pl.off_merge);
   p.partials = reinterpret_cast<float*>(ws + pl.off_partials);
+  p.q_heads = a.queue_set;
+  for (int x = 0; x < kQueues; ++x) {
+    p.q_base[x] = pl.q_base[x];
+    p.q_len[x] = pl.q_len[x];
+  }
   p.stage_seqs = reinterpret_cast<const StageSeq*>(image + pl.off_stage);
   p.stage_k = ws + pl.off_stage_k;
   p.stage_v = ws + pl.off_stage_v;

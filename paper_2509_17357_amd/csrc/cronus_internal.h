@@ -15,6 +15,10 @@ constexpr int kWaves = 8;
 constexpr int kNarrowRows = 32;     // one MFMA column tile: a decode's (token, head) rows
 constexpr int kWideKvTile = 64;     // keys staged in LDS per step of a wide (chunk) tile
 constexpr int kNarrowKvStep = 32 * kWaves;  // keys covered by the waves of a narrow item per step
+constexpr int kQueues = 8;          // work queues of a launch: one per XCD of an MI355X (each XCD has its own L2)
+constexpr int kCounterStride = 16;  // int32 between the queue heads of a set: one 64-byte line each
+constexpr int kQueueSetInts = (kQueues + 1) * kCounterStride;  // a set: the heads, then the count of finished work-groups
+constexpr int kQueueSets = 9;       // sets of queue heads per device: one per plan buffer of the ring, one for the static entry point
 
 // Per-sequence record of the batch (section 4.4: one iteration = chunks + decodes).
 struct SeqInfo {
@@ -37,7 +41,7 @@ struct WorkItem {
   int32_t partial;   // < 0: writes final output; else index of its (wide: first of kWaves) partial-result slot(s)
   int32_t wide;      // 1: chunk tile staged through LDS; >= 2: the same, reading the bf16 copy of an fp8
                      // sequence's K/V whose first block in the copy is wide - 2; 0: narrow (<= 32 rows),
-                     // waves split keys; -1: idle slot
+                     // waves split keys; -1: nothing to do (a work-group's "no item left" marker)
   // copy of the sequence's record, so that a work-group needs one dependent load less
   // before it can address Q and the block table
   int32_t prefix_len, chunk_len, q_off, n_blocks;
@@ -86,6 +90,12 @@ struct Plan {
   int32_t wide_rows = 0;  // rows per wide tile (compile-time choice of the kernel instance)
   int32_t n_stage_seqs = 0;
   int64_t n_stage_blocks = 0;
+  // The work items form kQueues queues, stored one after the other: queue x is items
+  // q_base[x] .. q_base[x] + q_len[x] - 1 in the order in which they should be taken.  The
+  // main kernel runs n_workgroups resident work-groups that take items from the queue of the
+  // XCD they run on until it is empty, then from the others.
+  int32_t q_base[kQueues] = {0}, q_len[kQueues] = {0};
+  int32_t n_workgroups = 0;
   // byte offsets inside the plan image (host-built metadata that the kernels read:
   // [WorkItem x n_items | MergeItem x n_merge | StageSeq x n_stage_seqs]) and its size
   size_t off_items = 0, off_merge = 0, off_stage = 0, image_bytes = 0;
@@ -119,6 +129,7 @@ struct AttnLaunch {
   const void* plan_image;  // device-visible [WorkItem | MergeItem | StageSeq] image at the plan's offsets
   const Plan* plan;
   void* stream;
+  int* queue_set;  // device; this call's set of queue heads (kQueueSetInts ints, all zero between launches)
   // optional hipEvent_t handles (measurement aid): [0], [1] start and stop of the main
   // kernel's dispatch; [2] start of the call's first kernel when that is another one (the
   // fp8 copy); [3] stop of its last kernel when that is another one (the merge)
@@ -137,6 +148,9 @@ int launch_attn(const AttnLaunch& a);
 // host data may be reused as soon as the call returns).
 constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
 int static_scratch_resolve(void** device_ptr);
+// Address, on the current device, of the library's kQueueSets sets of queue heads (a small
+// static device array, zero when the library is loaded; every launch leaves its set zero).
+int queue_sets_resolve(int** device_ptr);
 int static_scratch_upload(void* dst, const void* host_src, size_t bytes, void* stream);
 int launch_kv_append(const cronus_kv_cache* cache, const void* k_src, const void* v_src,
                      const int32_t* cu_tokens, const int32_t* start_pos, const int32_t* block_tables,

@@ -9,6 +9,7 @@
 // comparison sorts over items (narrow items are bucketed by length, the wide tiles of a
 // group are generated in cost order).
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <vector>
 
@@ -19,7 +20,7 @@ namespace {
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-constexpr int kXcds = 8;
+constexpr int kXcds = kQueues;
 
 struct Group {      // the wide tiles of one (sequence, KV head, head group): items [begin, end)
   int32_t begin, end;
@@ -34,6 +35,8 @@ struct Scratch {
   std::vector<MergeItem> merges;
   std::vector<StageSeq> stages;
   std::vector<int32_t> queue[kXcds];  // item references: >= 0 wide index, < 0 ~narrow index
+  struct Tile { int32_t t0, nt, kv_total, n_split, per, first_partial; float cost_per_key; };
+  std::vector<Tile> tiles;
   std::vector<int32_t> order, bucket_start;
 };
 
@@ -117,6 +120,66 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
     wide_piece_keys = (int)std::min<double>(std::max<double>(keys, kMinPiece), 1 << 30);
     wide_piece_keys = (wide_piece_keys + kWideKvTile - 1) / kWideKvTile * kWideKvTile;
   }
+  // A launch with few wide tiles (the paper's own iteration: one chunk of at most 512 tokens
+  // = 64 tiles, section 5.1) lives or dies by how its spans pack onto the CUs: 64 tiles in
+  // five spans each are 320 items for 256 CUs, two rounds where four spans each need one.
+  // Such a launch therefore picks its span length by estimated duration: for every way of
+  // cutting the longest tile into 1 .. 12 equal spans, the items and their times under a
+  // cost model fitted to per-work-group timestamps, scheduled as rounds over the CUs with
+  // the narrow items as filler, plus what the merge of the partial results costs.
+  if (wide_cost_total > 0 && wide_tiles <= 2LL * std::max(n_cus, 1)) {
+    const int cus = std::max(n_cus, 1);
+    // microseconds on MI355X (D = 128, bf16): a wide item that covers a span takes about
+    // 16 + 0.0223 per key at 256 rows (three quarters of that per key at half height), a
+    // narrow span 8 + 0.0096 per key; a partial slot costs the merge about 9 ns
+    const double wide_us0 = 16.0, wide_us_key = 0.0223, narrow_us0 = 8.0, narrow_us_key = 0.0096, slot_us = 0.009;
+    long long longest = 0;
+    for (int s = 0; s < n_seqs; ++s) {
+      const long long P = prefix_lens[s], C = chunk_lens[s];
+      if (C * group > kNarrowRows) longest = std::max(longest, P + C);
+    }
+    const double narrow_us = narrow_keys > 0
+        ? narrow_us_key * (double)narrow_keys + narrow_us0 * std::max<double>(1.0, (double)narrow_keys / 2048.0)
+        : 0.0;
+    double best_us = 0;
+    int best_piece = 0;
+    for (int cut = 1; cut <= 12; ++cut) {
+      int piece = (int)((longest + cut - 1) / cut);
+      piece = (piece + kWideKvTile - 1) / kWideKvTile * kWideKvTile;
+      if (cut > 1 && piece < kMinPiece) break;
+      long long items = 0, slots = 0;
+      double total_us = 0, longest_us = 0;
+      for (int s = 0; s < n_seqs; ++s) {
+        const long long P = prefix_lens[s], C = chunk_lens[s];
+        if (C * group <= kNarrowRows) continue;
+        for (long long t0 = 0; t0 < C; t0 += wide_tok) {
+          const long long nt = std::min<long long>(wide_tok, C - t0);
+          if (nt * group <= kNarrowRows) continue;
+          const long long kv_total = P + t0 + nt;
+          long long n_split = kv_total > piece + piece / 2 ? (kv_total + piece - 1) / piece : 1;
+          const long long per = ((kv_total + n_split - 1) / n_split + kWideKvTile - 1) / kWideKvTile * kWideKvTile;
+          n_split = (kv_total + per - 1) / per;
+          const double height = nt * group * 2 <= wide_rows ? 0.75 : 1.0;
+          const double us = wide_us0 + wide_us_key * height * (double)per;
+          const long long copies = (long long)Hkv * n_groups;
+          items += n_split * copies;
+          total_us += us * (double)(n_split * copies);
+          longest_us = std::max(longest_us, us);
+          if (n_split > 1) slots += n_split * copies * kWaves;
+        }
+      }
+      if (items == 0) break;
+      const long long rounds = (items + cus - 1) / cus;
+      const double wide_us = (double)(rounds - 1) * (total_us / (double)items) + longest_us;
+      const double fluid_us = (total_us + narrow_us) / cus;
+      const double us = std::max(wide_us, fluid_us) + slot_us * (double)slots + (slots ? 4.0 : 0.0);
+      if (best_piece == 0 || us < best_us) {
+        best_us = us;
+        best_piece = piece;
+      }
+    }
+    if (best_piece > 0) wide_piece_keys = best_piece;
+  }
   const long long target_items = std::max(n_cus, 1);  // about one span per CU: longer spans mean fewer work-group starts and fewer partial results to merge (measured: 6 % on the Llama-3-8B-shaped batch against four per CU)
   long long span = (narrow_keys + target_items - 1) / target_items;
   span = (span + kNarrowKvStep - 1) / kNarrowKvStep * kNarrowKvStep;
@@ -176,7 +239,6 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
           add_narrow(s, kvh, head0, nh, 0, C, P + C);
           continue;
         }
-        Group g{(int32_t)sc.wide.size(), 0, 0.f};
         int32_t wide_tag = 1;
         const int seq_tiles = (C + wide_tok - 1) / wide_tok;
         if (fp8 && (seq_tiles >= kStageMinTiles || (seq_tiles >= kStageMinTilesLong && P + C >= kStageLongKeys))) {
@@ -188,6 +250,9 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
           }
           if (!sc.stages.empty() && sc.stages.back().seq == s) wide_tag = 2 + sc.stages.back().blk0;
         }
+        // the tiles of this (sequence, KV head, head group), shortest first
+        sc.tiles.clear();
+        int max_split = 0;
         for (int t0 = 0; t0 < C; t0 += wide_tok) {
           const int nt = std::min(wide_tok, C - t0);
           if (nt * group <= kNarrowRows) {
@@ -199,41 +264,45 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
           // each span leaves partial results (one slot per wavefront) for the merge.
           const int kv_total = P + t0 + nt;
           const float rows_frac = std::max(0.25f, (float)(nt * nh) / wide_rows);
-          const float cost_per_key = (wide_rows / 128.0f) * rows_frac;
           int n_split = 1;
           if (wide_piece_keys > 0 && kv_total > wide_piece_keys + wide_piece_keys / 2)
             n_split = (kv_total + wide_piece_keys - 1) / wide_piece_keys;
           const int per = ((kv_total + n_split - 1) / n_split + kWideKvTile - 1) / kWideKvTile * kWideKvTile;
           n_split = (kv_total + per - 1) / per;
           const int rows = nt * nh;
+          int32_t first_partial = -1;
           if (n_split > 1) {
+            first_partial = (int32_t)n_partials;
             for (int wv = 0; wv * kNarrowRows < rows; ++wv)
-              sc.merges.push_back(MergeItem{(int32_t)n_partials + wv, n_split, s, kvh, head0, nh, t0, nt,
+              sc.merges.push_back(MergeItem{first_partial + wv, n_split, s, kvh, head0, nh, t0, nt,
                                             wv * kNarrowRows, std::min(kNarrowRows, rows - wv * kNarrowRows), kWaves, 0});
             n_merge_rows += rows;
+            n_partials += (int64_t)n_split * kWaves;
           }
-          for (int i = 0; i < n_split; ++i) {
+          sc.tiles.push_back(Scratch::Tile{t0, nt, kv_total, n_split, per, first_partial, (wide_rows / 128.0f) * rows_frac});
+          max_split = std::max(max_split, n_split);
+        }
+        // One group per span index: the spans i of all tiles of this (sequence, KV head) cover
+        // nearly the same keys, so they are queued together (on one XCD, whose L2 then serves
+        // the K/V blocks to all of them); different spans share nothing and may go elsewhere.
+        for (int i = 0; i < max_split; ++i) {
+          Group g{(int32_t)sc.wide.size(), 0, 0.f};
+          for (const Scratch::Tile& t : sc.tiles) {
+            if (i >= t.n_split) continue;
             WorkItem w{};
-            w.seq = s; w.kv_head = kvh; w.head0 = head0; w.n_heads = nh; w.q_tok0 = t0; w.n_tok = nt;
-            w.kv_begin = i * per;
-            w.kv_end = std::min(kv_total, (i + 1) * per);
-            w.partial = -1;
-            if (n_split > 1) {
-              w.partial = (int32_t)n_partials;
-              n_partials += kWaves;
-            }
+            w.seq = s; w.kv_head = kvh; w.head0 = head0; w.n_heads = nh; w.q_tok0 = t.t0; w.n_tok = t.nt;
+            w.kv_begin = i * t.per;
+            w.kv_end = std::min(t.kv_total, (i + 1) * t.per);
+            w.partial = t.n_split > 1 ? t.first_partial + i * kWaves : -1;
             w.wide = wide_tag;
-            const float cost = (float)(w.kv_end - w.kv_begin) * cost_per_key;
+            const float cost = (float)(w.kv_end - w.kv_begin) * t.cost_per_key;
             sc.wide.push_back(w);
             sc.wide_cost.push_back(cost);
             g.cost += cost;
           }
-        }
-        g.end = (int32_t)sc.wide.size();
-        if (pair_tiles && g.end - g.begin >= 2) {
-          bool whole = true;  // tiles cut into spans stay single
-          for (int i = g.begin; i < g.end; ++i) whole = whole && sc.wide[(size_t)i].partial < 0;
-          if (whole) {
+          g.end = (int32_t)sc.wide.size();
+          if (pair_tiles && max_split == 1 && g.end - g.begin >= 2) {
+            // (tiles cut into spans stay single)
             // tiles were generated shortest first: the k-th longest takes the k-th shortest
             const int n = g.end - g.begin, n_pairs = n / 2;
             for (int k = 0; k < n_pairs; ++k) {
@@ -248,20 +317,20 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
             sc.wide_cost.erase(sc.wide_cost.begin() + g.begin, sc.wide_cost.begin() + g.begin + n_pairs);
             g.end -= n_pairs;
           }
+          if (g.end > g.begin) sc.groups.push_back(g);
         }
-        if (g.end > g.begin) sc.groups.push_back(g);
       }
     }
   }
 
-  // Order for the grid.  Work-group i runs on XCD i % 8 (each XCD has its own L2) and an
-  // XCD takes its work-groups in index order.  All wide tiles of one (sequence, KV head)
-  // read the same K/V blocks, so they are queued on one XCD, back to back, longest first
-  // (they were generated shortest first), where the 32 CUs of that XCD run them side by
-  // side and share the blocks through its L2.  Groups go to the least loaded XCD, longest
-  // group first; narrow items (no reuse), longest first, even out the queues; the two kinds
-  // may then be interleaved (below).  Queues are padded to one length with idle items
-  // (wide = -1).
+  // Order of the work.  The main kernel's work-groups stay resident (one per CU) and take
+  // items from the queue of the XCD they run on, in queue order, and from the other queues
+  // once their own is empty (each XCD has its own L2).  The wide tiles of one (sequence, KV
+  // head, span) read the same K/V blocks, so they are queued on one XCD, back to back,
+  // longest first (they were generated shortest first), where the 32 CUs of that XCD run
+  // them side by side and share the blocks through its L2.  Groups go to the least loaded
+  // queue, longest group first; narrow items (no reuse), longest first, even out the queues;
+  // the two kinds may then be interleaved (below).
   double load[kXcds] = {0};
   for (auto& q : sc.queue) q.clear();
   // Given equal work, the odd-numbered XCDs of an MI355X finished later than the
@@ -352,19 +421,16 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
       q[k++] = ref;
     }
   }
-  size_t qlen = 0;
-  for (const auto& q : sc.queue) qlen = std::max(qlen, q.size());
-  const size_t n_real = sc.wide.size() + sc.narrow.size();
-  size_t n_slots = 0;
-  if (n_real) {
-    n_slots = qlen * kXcds;
-    // trailing idle slots are dropped
-    while (n_slots > 0) {
-      const size_t k = (n_slots - 1) / kXcds, x = (n_slots - 1) % kXcds;
-      if (k < sc.queue[x].size()) break;
-      --n_slots;
+  const size_t n_slots = sc.wide.size() + sc.narrow.size();
+  {
+    int32_t base = 0;
+    for (int x = 0; x < kQueues; ++x) {
+      plan->q_base[x] = base;
+      plan->q_len[x] = (int32_t)sc.queue[x].size();
+      base += plan->q_len[x];
     }
   }
+  plan->n_workgroups = (int32_t)std::min<size_t>(n_slots, (size_t)std::max(n_cus, 1));
 
   plan->n_seqs = n_seqs;
   plan->wide_rows = wide_rows;
@@ -392,26 +458,19 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
 void write_plan(const Plan* plan, void* host_buf) {
   // copies the work list that the last build_plan() of this thread left in its scratch
   Scratch& sc = scratch();
-  const size_t n_slots = (size_t)plan->n_items;
   unsigned char* h = static_cast<unsigned char*>(host_buf);
   // (the per-sequence records travel inside the work and merge items; the kernels read nothing else)
   WorkItem* wi = reinterpret_cast<WorkItem*>(h + plan->off_items);
-  WorkItem idle{};
-  idle.wide = -1;
-  idle.partial = -1;
-  for (size_t i = 0; i < n_slots; ++i) {
-    const size_t k = i / kXcds, x = i % kXcds;
-    if (k < sc.queue[x].size()) {
-      const int32_t ref = sc.queue[x][k];
+  size_t i = 0;
+  for (int x = 0; x < kQueues; ++x) {
+    for (const int32_t ref : sc.queue[x]) {
       WorkItem w = ref >= 0 ? sc.wide[(size_t)ref] : sc.narrow[(size_t)~ref];
       const SeqInfo& si = sc.seqs[(size_t)w.seq];
       w.prefix_len = si.prefix_len;
       w.chunk_len = si.chunk_len;
       w.q_off = si.q_off;
       w.n_blocks = si.n_blocks;
-      wi[i] = w;
-    } else {
-      wi[i] = idle;
+      wi[i++] = w;
     }
   }
   if (!sc.merges.empty()) {

@@ -74,7 +74,7 @@ def test_long_decode_is_split_and_merged():
 SPLIT_WIDE = [
     # (shape, prefix_lens, chunk_lens): few wide tiles with many keys -> key spans + merge
     (W.SHAPE_8B, [3000, 40], [100, 1]),                       # last span holds the causal edge
-    (W.SHAPE_8B, [1700], [130]),                              # two wide tiles and a narrow tail of two tokens
+    (W.SHAPE_8B, [2500], [130]),                              # two wide tiles and a narrow tail of two tokens
     (W.HeadShape(8, 2, 64), [2500, 777], [70, 1]),            # D = 64
     (W.HeadShape(28, 4, 128), [1900], [80]),                  # G = 7: wavefronts start inside a token
     (W.HeadShape(16, 2, 128, "fp8"), [2100, 300], [64, 1]),   # fp8 cache (register-staged wide path)

@@ -1,7 +1,7 @@
 """The host-side work decomposition (no GPU): every (sequence, q head, chunk token)
 must be covered by exactly one chain of items whose key ranges partition [0, prefix +
 token + 1) up to the tile's own causal end, spans must be aligned to what the kernel
-assumes, and idle slots must be inert."""
+assumes, and the items must be listed queue by queue."""
 import numpy as np
 import pytest
 
@@ -30,8 +30,10 @@ def check_plan(shape, P, C):
 def verify_items(shape, P, C, items, stats):
     """The invariants of a work list (whatever planner options or CU count produced it)."""
     G = shape.n_q_heads // shape.n_kv_heads
-    real = items[items[:, F["wide"]] >= 0]
-    assert (items[items[:, F["wide"]] < 0][:, :8] == 0).all()  # idle slots carry nothing
+    real = items
+    assert (items[:, F["wide"]] >= 0).all()                       # every listed item is work
+    assert (np.diff(items[:, F["queue"]]) >= 0).all() and items[:, F["queue"]].min(initial=0) >= 0 \
+        and items[:, F["queue"]].max(initial=0) <= 7                # queue by queue
     assert (real[:, F["wide"]] >= 1).sum() == stats["wide_items"]
     # coverage[s][head, token] = list of (kv_begin, kv_end, partial)
     cover = {}
@@ -98,11 +100,11 @@ def test_plan_edge_cases():
 
 
 def test_plan_queues_follow_xcd_order():
-    """Work-group i runs on XCD i % 8: the wide tiles of one (sequence, KV head) sit in few
-    queues, and within a queue they come longest first."""
+    """One queue per XCD: the wide tiles of one (sequence, KV head) sit in few queues, and
+    within a queue they come longest first."""
     b = W.draw_batch(3)
     items, _ = plan_for(b.shape, b.prefix_lens, b.chunk_lens)
-    wide = [(i % 8, it) for i, it in enumerate(items) if it[F["wide"]] >= 1]
+    wide = [(int(it[F["queue"]]) % 8, it) for it in items if it[F["wide"]] >= 1]
     queues_of = {}
     for x, it in wide:
         queues_of.setdefault((int(it[F["seq"]]), int(it[F["kv_head"]])), set()).add(x)
@@ -110,19 +112,19 @@ def test_plan_queues_follow_xcd_order():
     for x in range(8):
         last = {}
         for xx, it in wide:
-            if xx != x:
+            if xx != x or it[F["kv_begin"]] > 0:
                 continue
             key = (int(it[F["seq"]]), int(it[F["kv_head"]]))
             if key in last:
-                assert it[F["kv_end"]] <= last[key]
-            last[key] = int(it[F["kv_end"]])
+                assert it[F["q_tok0"]] < last[key]        # the latest tile (the most keys) first
+            last[key] = int(it[F["q_tok0"]])
     # the eight queues carry similar amounts of work
     load = np.zeros(8)
-    for i, it in enumerate(items):
+    for it in items:
         if it[F["wide"]] >= 1:
-            load[i % 8] += 2.0 * (it[F["kv_end"]] - it[F["kv_begin"]])
+            load[it[F["queue"]] % 8] += 2.0 * (it[F["kv_end"]] - it[F["kv_begin"]])
         elif it[F["wide"]] == 0:
-            load[i % 8] += 0.5 * (it[F["kv_end"]] - it[F["kv_begin"]])
+            load[it[F["queue"]] % 8] += 0.5 * (it[F["kv_end"]] - it[F["kv_begin"]])
     assert load.max() <= 1.1 * load.mean()
 
 

@@ -64,7 +64,7 @@ def run_cases(exe, lines):
             replies.append({"rc": int(f[1]), "l_p": int(f[2]), "tp": float(f[3]), "tc": float(f[4])})
     for rep in replies:
         if "items" in rep:
-            rep["items"] = np.array(rep["items"], dtype=np.int32).reshape(-1, 12)
+            rep["items"] = np.array(rep["items"], dtype=np.int32).reshape(-1, 13)
     return replies
 
 
