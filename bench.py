@@ -36,7 +36,7 @@ sys.path.insert(0, ROOT)
 WORKLOADS = {"tiny": 1, "llama3_8b": 2, "prefill_heavy": 3, "decode_heavy": 4, "llama_70b_fp8": 5,
              "paper_iteration_16k": "paper:32/8/128", "paper_iteration_16k_g7": "paper:28/4/128"}
 HEADLINE = "prefill_heavy"
-CLOCK_SETTLE_MS = 60.0         # untimed work before the warm-up steps: clocks of an idle GPU rise over tens of ms
+CLOCK_SETTLE_MS = 150.0        # untimed work before the warm-up steps: the clocks of a GPU that idled take tens of ms of load to settle
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 # which roofline bounds the attention kernel on each workload (KV bytes vs visible-pair flops)
@@ -82,31 +82,33 @@ def time_workload(name, steps, warmup, trial=0):
     torch.cuda.synchronize()
     stats = B.cronus_attn_mixed_plan_stats(it.cache, batch.prefix_lens, batch.chunk_lens)
 
-    # let the clocks of an idle GPU settle (untimed, not counted as warm-up steps), then the W warm-up steps
-    t_settle = time.perf_counter()
-    while (time.perf_counter() - t_settle) * 1e3 < CLOCK_SETTLE_MS:
-        for _ in range(8):
-            it.step()
-        torch.cuda.synchronize()
-    for _ in range(warmup):
-        it.step()
-    torch.cuda.synchronize()
-
-    # four events per timed step: start/stop of the main kernel's own dispatch, start of the
-    # call's first kernel if that is the fp8 copy, stop of its last if that is the merge
-    ev = B.HipEvents()
-    quads = [tuple(ev.create() for _ in range(4)) for _ in range(steps)]
-    for q in quads:  # first use of an event is slow (lazy allocation): keep it out of the timed region
-        B.cronus_profile_events(*q)
-        it.attention()
-    B.cronus_profile_events(None, None)
-    torch.cuda.synchronize()
-    # The interpreter's cyclic garbage collector stays out of the timed region: with torch
-    # imported one full collection takes 30-40 ms, twice the 100 timed steps of the default
-    # run, and whether one falls into them changed from run to run (0.18 or 0.5 ms/step).
+    # The interpreter's cyclic garbage collector stays out of everything from here to the end of
+    # the timed region: with torch imported one full collection takes 30-40 ms of host time during
+    # which the GPU idles and its clocks drop; the launches that follow then run up to 20 % slower
+    # and take some twenty launches to recover (a collection between warm-up and timed steps was
+    # what made short runs of this file read 5-10 % below long ones).
     gc.collect()
     gc.disable()
     try:
+        # four events per timed step: start/stop of the main kernel's own dispatch, start of the
+        # call's first kernel if that is the fp8 copy, stop of its last if that is the merge
+        ev = B.HipEvents()
+        quads = [tuple(ev.create() for _ in range(4)) for _ in range(steps)]
+        for q in quads:  # first use of an event is slow (lazy allocation): keep it out of the timed region
+            B.cronus_profile_events(*q)
+            it.attention()
+        B.cronus_profile_events(None, None)
+        torch.cuda.synchronize()
+        # let the clocks settle under this workload (untimed, not counted as warm-up steps),
+        # then the W warm-up steps, then, with nothing but a synchronisation between, the K timed steps
+        t_settle = time.perf_counter()
+        while (time.perf_counter() - t_settle) * 1e3 < CLOCK_SETTLE_MS:
+            for _ in range(8):
+                it.step()
+            torch.cuda.synchronize()
+        for _ in range(warmup):
+            it.step()
+        torch.cuda.synchronize()
         t0 = time.perf_counter()
         for q in quads:
             B.cronus_profile_events(*q)
@@ -144,6 +146,7 @@ def time_workload(name, steps, warmup, trial=0):
         # the main kernel alone (what a profiler's kernel trace lists as attn_mixed_kernel)
         "attn_kernel_ms": main_mean, "attn_kernel_ms_median": float(np.median(main_ms)),
         "attn_kernel_ms_min": float(main_ms.min()),
+        "attn_ms_first_to_last": [round(float(x), 4) for x in (span_ms if steps <= 40 else span_ms[:: max(1, steps // 40)])],
         "attn_tflops": flops / 1e12 / (span_mean * 1e-3),
         "attn_gbs": abytes / 1e9 / (span_mean * 1e-3),
         "pct_mfma_peak": 100.0 * flops / 1e12 / (span_mean * 1e-3) / PEAK_BF16_TFLOPS,
