@@ -47,9 +47,9 @@ BOUND = {"tiny": "hbm", "llama3_8b": "hbm", "prefill_heavy": "mfma", "decode_hea
 # 2.000, WRITE_SIZE x 1.000).  These are STATIC figures copied from the summary named below, taken
 # with the library version named below; with any other library version the line carries null.
 TRAFFIC_SOURCE = "profiles/attn_mixed_kernel_benchmark_batches_rocprofv3.md"
-TRAFFIC_LIB_VERSION = 200
-MEASURED_TRAFFIC_BYTES = {"llama3_8b": 624460157, "prefill_heavy": 568301344, "decode_heavy": 4868596580,
-                          "llama_70b_fp8": 3998651460}
+TRAFFIC_LIB_VERSION = 500
+MEASURED_TRAFFIC_BYTES = {"llama3_8b": 624308862, "prefill_heavy": 566885879, "decode_heavy": 4868675563,
+                          "llama_70b_fp8": 4022134638, "paper_iteration_16k": 285002891}
 
 
 def make_batch(name, trial=0):
@@ -175,6 +175,31 @@ def time_workload(name, steps, warmup, trial=0):
     return res, batch
 
 
+def time_mfma_probe(iters=4000, reps=5):
+    """What rate of v_mfma_f32_32x32x16_bf16 this GPU sustains when every CU issues nothing else
+    (cronus_probe_mfma): with operand registers that hold small constants, and with random bf16
+    values.  Context for the MFMA roofline fractions: the published peak assumes the nominal
+    clock, which the GPU does not hold under a chip-wide MFMA load on real data."""
+    import torch
+    from paper_2509_17357_amd import binding as B
+    sink = torch.empty(B.cronus_probe_mfma_sink_floats(), dtype=torch.float32, device="cuda:0")
+    stream = torch.cuda.current_stream().cuda_stream
+    out = {"instruction": "v_mfma_f32_32x32x16_bf16", "wavefronts_per_cu": 8, "mfma_per_wavefront": 32 * iters}
+    for name, rnd in (("constant_operands", False), ("random_operands", True)):
+        for _ in range(3):
+            flops = B.cronus_probe_mfma(rnd, iters, sink, stream=stream)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            B.cronus_probe_mfma(rnd, iters, sink, stream=stream)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        out[name] = {"ms": ms, "tflops": flops / 1e12 / (ms * 1e-3), "frac_of_peak": flops / 1e12 / (ms * 1e-3) / PEAK_BF16_TFLOPS}
+    return out
+
+
 def time_scatter_gather(reps=5):
     """cronus_kv_append and cronus_kv_gather as pure data movement: the decode contexts of
     the decode-heavy batch (about 1.2 M tokens, 4.8 GB of K+V) scattered into the paged pool
@@ -279,6 +304,7 @@ def main():
     ap.add_argument("--workload", default=HEADLINE, choices=sorted(WORKLOADS))
     ap.add_argument("--no-extra", action="store_true", help="time the headline workload only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--mfma-probe", action="store_true", help="run only the MFMA rate probe (cronus_probe_mfma)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device copy (reference for the FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -301,12 +327,18 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "launches": max(1, args.steps)}))
         return
 
+    if args.mfma_probe:
+        print(json.dumps({"mfma_probe": time_mfma_probe()}))
+        return
+
     main_res, batch = time_workload(args.workload, args.steps, args.warmup)
     if not args.no_cpu_baseline:
         main_res["cpu_baseline"] = cpu_baseline(batch)
     others = {}
     scatter_gather = None
+    mfma_probe = None
     if not args.no_extra:
+        mfma_probe = time_mfma_probe()
         # every workload with the same K timed launches after the same settle phase and W warm-up steps
         for name in ("llama3_8b", "prefill_heavy", "decode_heavy", "llama_70b_fp8", "paper_iteration_16k",
                      "paper_iteration_16k_g7"):
@@ -317,6 +349,12 @@ def main():
                 others[name]["cpu_baseline"] = cpu_baseline(b, budget_s=3.0, min_s=2.5)
             del b
         scatter_gather = time_scatter_gather()
+    if mfma_probe is not None:
+        # context, not the roofline: the fraction of what plain MFMA issue sustains on this GPU, on random data
+        for res in [main_res, *others.values()]:
+            if res["roofline"]["bound"] == "mfma":
+                res["roofline"]["mfma_probe_tflops"] = mfma_probe["random_operands"]["tflops"]
+                res["roofline"]["frac_of_mfma_probe"] = res["roofline"]["achieved"] / mfma_probe["random_operands"]["tflops"]
     sh = batch.shape
     line = {
         "metric": "mixed-batch attention tokens/s; TFLOP/s and HBM GB/s as % of MI355X peak",
@@ -340,6 +378,7 @@ def main():
         "roofline": main_res["roofline"],
         "other_workloads": others,
         "scatter_gather": scatter_gather,
+        "mfma_probe": mfma_probe,
     }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = main_res["cpu_baseline"]

@@ -284,6 +284,26 @@ int cronus_balancer_split(const cronus_balancer_model* model, int64_t l_in, int6
  */
 void cronus_profile_events(void* main_start, void* main_stop, void* first_start, void* last_stop);
 
+/*
+ * cronus_probe_mfma - measurement aid, not part of the attention path: the rate of
+ * v_mfma_f32_32x32x16_bf16 (the instruction of both products of cronus_attn_mixed) that the
+ * current GPU sustains when every CU issues nothing else.  Enqueues one kernel on hip_stream:
+ * one work-group of 8 wavefronts per CU, each wavefront issuing iters x 32 independent MFMAs
+ * on operand registers that hold small integer bit patterns (random_operands = 0) or random
+ * bf16 values of magnitude 1/16 .. 1 (random_operands != 0: the switching activity of real
+ * data; the clock a GPU holds under this load depends on it).  *flops_host receives the
+ * floating-point operations of the launch (2 x 32 x 32 x 16 per MFMA); the caller times the
+ * launch with events on the stream.  sink: DEVICE buffer of at least sink_floats floats that
+ * receives the accumulators (one float per thread; cronus_probe_mfma_sink_floats()).
+ * Returns CRONUS_OK, INVALID_ARG (iters < 1 or > 1 << 20, null pointers), WORKSPACE (sink
+ * smaller than cronus_probe_mfma_sink_floats()), ERR_HIP.
+ */
+int cronus_probe_mfma(int random_operands, int iters, float* sink, size_t sink_floats, void* hip_stream,
+                      double* flops_host);
+
+/* Floats the sink of cronus_probe_mfma must hold on the current device (CUs x 512). */
+size_t cronus_probe_mfma_sink_floats(void);
+
 /* Static, NUL-terminated description of a cronus_status. */
 const char* cronus_status_string(int status);
 

@@ -26,7 +26,8 @@ CRONUS_KV_FP8_E4M3 = 1
 EXPORTS = ("cronus_kv_append", "cronus_kv_gather", "cronus_attn_mixed", "cronus_attn_mixed_static",
            "cronus_attn_mixed_workspace_bytes",
            "cronus_attn_mixed_plan_stats", "cronus_attn_mixed_plan_items", "cronus_balancer_split",
-           "cronus_profile_events", "cronus_status_string", "cronus_version")
+           "cronus_profile_events", "cronus_probe_mfma", "cronus_probe_mfma_sink_floats", "cronus_status_string",
+           "cronus_version")
 
 
 class cronus_kv_cache(ctypes.Structure):
@@ -83,6 +84,10 @@ def lib() -> ctypes.CDLL:
         L.cronus_attn_mixed_plan_items.restype = ctypes.c_int64
         L.cronus_profile_events.argtypes = [vp, vp, vp, vp]
         L.cronus_profile_events.restype = None
+        L.cronus_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t, vp, ctypes.POINTER(ctypes.c_double)]
+        L.cronus_probe_mfma.restype = ctypes.c_int
+        L.cronus_probe_mfma_sink_floats.argtypes = []
+        L.cronus_probe_mfma_sink_floats.restype = ctypes.c_size_t
         L.cronus_status_string.argtypes = [ctypes.c_int]
         L.cronus_status_string.restype = ctypes.c_char_p
         L.cronus_version.argtypes = []
@@ -176,6 +181,25 @@ def cronus_kv_gather(cache: cronus_kv_cache, k_dst, v_dst, cu_tokens, start_pos,
     if check and rc != CRONUS_OK:
         raise CronusError(rc, "cronus_kv_gather")
     return rc
+
+
+def cronus_probe_mfma(random_operands: bool, iters: int, sink, sink_floats=None, stream: int = 0, check=True):
+    """Enqueues the MFMA rate probe; returns the floating-point operations of the launch.
+    sink: device float32 tensor (or address + sink_floats) of at least cronus_probe_mfma_sink_floats() elements."""
+    flops = ctypes.c_double(0.0)
+    if sink_floats is None:
+        sink_floats = sink.numel() if hasattr(sink, "numel") else 0
+    rc = lib().cronus_probe_mfma(int(bool(random_operands)), int(iters), _ptr(sink), int(sink_floats),
+                                 ctypes.c_void_p(stream), ctypes.byref(flops))
+    if rc != CRONUS_OK:
+        if check:
+            raise CronusError(rc, "cronus_probe_mfma")
+        return rc
+    return flops.value
+
+
+def cronus_probe_mfma_sink_floats() -> int:
+    return int(lib().cronus_probe_mfma_sink_floats())
 
 
 def cronus_balancer_split(l_in: int, n_d: int, l_ctxd: int, n_free: int, k_p: float, b_p: float, k_ctxp: float,

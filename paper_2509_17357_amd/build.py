@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcronus.so")
-SOURCES = ["api.cpp", "plan.cpp", "balancer.cpp", "kv_append.hip", "kv_gather.hip", "attn_mixed.hip"]
+SOURCES = ["api.cpp", "plan.cpp", "balancer.cpp", "kv_append.hip", "kv_gather.hip", "attn_mixed.hip", "mfma_probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-x", "hip"]
 

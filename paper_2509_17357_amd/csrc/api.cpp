@@ -154,6 +154,16 @@ int cronus_kv_gather(const cronus_kv_cache* cache, void* k_dst, void* v_dst, con
                           n_tokens, hip_stream);
 }
 
+size_t cronus_probe_mfma_sink_floats(void) { return (size_t)mfma_probe_sink_floats(device_cus()); }
+
+int cronus_probe_mfma(int random_operands, int iters, float* sink, size_t sink_floats, void* hip_stream,
+                      double* flops_host) {
+  if (iters < 1 || iters > (1 << 20) || !sink || !flops_host) return CRONUS_ERR_INVALID_ARG;
+  const int n_cus = device_cus();
+  if (sink_floats < (size_t)mfma_probe_sink_floats(n_cus)) return CRONUS_ERR_WORKSPACE;
+  return launch_mfma_probe(random_operands, iters, n_cus, sink, hip_stream, flops_host);
+}
+
 size_t cronus_attn_mixed_workspace_bytes(const cronus_kv_cache* cache, const int32_t* prefix_lens,
                                          const int32_t* chunk_lens, int32_t n_seqs) {
   if (check_shape(cache) || n_seqs < 0 || (n_seqs > 0 && (!prefix_lens || !chunk_lens))) return 0;

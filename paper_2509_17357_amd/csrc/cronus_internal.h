@@ -159,4 +159,8 @@ int launch_kv_gather(const cronus_kv_cache* cache, void* k_dst, void* v_dst, con
                      const int32_t* start_pos, const int32_t* block_tables, int32_t max_blocks_per_seq,
                      int32_t n_seqs, int32_t n_tokens, void* stream);
 
+// mfma_probe.hip (measurement aid)
+int launch_mfma_probe(int random_operands, int iters, int n_cus, float* sink, void* stream, double* flops);
+int mfma_probe_sink_floats(int n_cus);
+
 }  // namespace cronus

@@ -56,6 +56,13 @@ def test_argument_checks_without_a_device():
     # null cache pointers are rejected before anything touches a device
     assert B.cronus_attn_mixed(c, 0, 0, [1], [1], 0, 1, 0.125, 0, 0, check=False) == B.CRONUS_ERR_INVALID_ARG
     assert B.cronus_kv_append(c, 0, 0, 0, 0, 0, 1, 1, 1, check=False) == B.CRONUS_ERR_INVALID_ARG
+    # the MFMA rate probe: iteration count, null sink, a sink that is too small (made-up address, never used)
+    need = B.cronus_probe_mfma_sink_floats()
+    assert need == 256 * 512  # without a device the library assumes MI355X's 256 CUs
+    assert B.cronus_probe_mfma(True, 0, 0x1000, need, check=False) == B.CRONUS_ERR_INVALID_ARG
+    assert B.cronus_probe_mfma(True, (1 << 20) + 1, 0x1000, need, check=False) == B.CRONUS_ERR_INVALID_ARG
+    assert B.cronus_probe_mfma(True, 10, 0, need, check=False) == B.CRONUS_ERR_INVALID_ARG
+    assert B.cronus_probe_mfma(False, 10, 0x1000, need - 1, check=False) == B.CRONUS_ERR_WORKSPACE
 
 
 def test_workload_recipes():

@@ -59,3 +59,29 @@ def test_timed_launch_matches_untimed(dtype):
         B.cronus_profile_events(None, None)
         for e in (start, stop, first, last):
             ev.destroy(e)
+
+
+def test_mfma_probe_runs_and_reports_its_work():
+    """The MFMA rate probe (measurement aid): the reported operation count is that of the launch,
+    the accumulators come back finite (zero for the constant bit patterns, which are bf16
+    denormals; non-zero for random operands), and the rate lies below the published peak."""
+    need = B.cronus_probe_mfma_sink_floats()
+    n_cus = torch.cuda.get_device_properties(0).multi_processor_count
+    assert need == n_cus * 512
+    sink = torch.full((need,), float("nan"), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    iters = 200
+    for rnd in (False, True):
+        sink.fill_(float("nan"))
+        flops = B.cronus_probe_mfma(rnd, iters, sink, stream=stream)
+        assert flops == 2.0 * 32 * 32 * 16 * 32 * iters * 8 * n_cus
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(sink).all())
+        assert bool((sink != 0).any()) == rnd
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        B.cronus_probe_mfma(rnd, 2000, sink, stream=stream)
+        e1.record()
+        torch.cuda.synchronize()
+        tflops = flops * 10 / 1e12 / (e0.elapsed_time(e1) * 1e-3)
+        assert 200.0 < tflops < 2600.0, tflops
