@@ -1204,35 +1204,64 @@ __global__ __launch_bounds__(kStageThreads) void kv_stage_kernel(AttnParams p) {
 
 // Combine the partial results of a row group that was split over key spans:
 // out = sum_s O_s 2^(m_s - M) / sum_s l_s 2^(m_s - M), M = max_s m_s (m in log2 units).
-// D/4 threads share a row (four dims each), so a work-group of 256 threads combines
-// 1024/D rows at a time; the loads of the spans are independent of each other.
+// D/4 threads share a row (four dims each); a work-group of 256 threads covers 1024/D rows
+// per pass and keeps all passes of the item's (at most 32) rows in flight at once, so the
+// loads of a span for every row are issued together: the kernel is bound by memory
+// latency (a row's spans are combined in span order, the sums depend on each other).
 constexpr int kMergeThreads = 256;
 template <int D, bool FP8>
 __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(AttnParams p) {
-  constexpr int TPR = D / 4, RPP = kMergeThreads / TPR;
+  constexpr int TPR = D / 4, RPP = kMergeThreads / TPR, NPASS = kNarrowRows / RPP;
+  static_assert(NPASS * RPP == kNarrowRows, "a merge item has at most kNarrowRows rows");
   const MergeItem mi = p.merges[blockIdx.x];
   const int dq = threadIdx.x % TPR;
   const size_t slot = (size_t)kNarrowRows * (D + 2);
   const size_t step = slot * (size_t)mi.stride;
   const float vmul = FP8 ? p.v_scale[mi.kv_head] : 1.0f;
   const float* base = p.partials + (size_t)mi.first_partial * slot;
-  for (int r = threadIdx.x / TPR; r < mi.n_rows; r += RPP) {
-    float mt = kNeg * 4.f;
-    for (int s = 0; s < mi.n_split; ++s) mt = fmaxf(mt, base[s * step + kNarrowRows * D + r]);
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    float ls = 0.f;
-    for (int s = 0; s < mi.n_split; ++s) {
-      const float* ps = base + s * step;
-      const float w = __builtin_amdgcn_exp2f(ps[kNarrowRows * D + r] - mt);
-      const f32x4 o4 = *reinterpret_cast<const f32x4*>(ps + r * D + 4 * dq);
-      acc += o4 * w;
-      ls += ps[kNarrowRows * D + kNarrowRows + r] * w;
+  int row[NPASS];  // clamped: rows past the item's last repeat it (loaded, never stored)
+#pragma unroll
+  for (int k = 0; k < NPASS; ++k) row[k] = min((int)threadIdx.x / TPR + k * RPP, mi.n_rows - 1);
+  float mt[NPASS];
+#pragma unroll
+  for (int k = 0; k < NPASS; ++k) mt[k] = kNeg * 4.f;
+  for (int s = 0; s < mi.n_split; ++s) {
+#pragma unroll
+    for (int k = 0; k < NPASS; ++k) mt[k] = fmaxf(mt[k], base[s * step + kNarrowRows * D + row[k]]);
+  }
+  f32x4 acc[NPASS];
+  float ls[NPASS];
+#pragma unroll
+  for (int k = 0; k < NPASS; ++k) {
+    acc[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+    ls[k] = 0.f;
+  }
+  for (int s = 0; s < mi.n_split; ++s) {
+    const float* ps = base + s * step;
+    float ms[NPASS], lsp[NPASS];
+    f32x4 o4[NPASS];
+#pragma unroll
+    for (int k = 0; k < NPASS; ++k) {
+      ms[k] = ps[kNarrowRows * D + row[k]];
+      o4[k] = *reinterpret_cast<const f32x4*>(ps + row[k] * D + 4 * dq);
+      lsp[k] = ps[kNarrowRows * D + kNarrowRows + row[k]];
     }
+#pragma unroll
+    for (int k = 0; k < NPASS; ++k) {
+      const float w = __builtin_amdgcn_exp2f(ms[k] - mt[k]);
+      acc[k] += o4[k] * w;
+      ls[k] += lsp[k] * w;
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < NPASS; ++k) {
+    const int r = (int)threadIdx.x / TPR + k * RPP;
+    if (r >= mi.n_rows) continue;
     const int tr = mi.row0 + r;
     const int t = tr / mi.n_heads, gi = tr - t * mi.n_heads;
     unsigned short* op = p.out + ((long long)(mi.q_off + mi.q_tok0 + t) * p.n_q_heads + mi.head0 + gi) * D + 4 * dq;
-    const float f = vmul / ls;
-    u32x2 w2 = {pack_bf16(acc[0] * f, acc[1] * f), pack_bf16(acc[2] * f, acc[3] * f)};
+    const float f = vmul / ls[k];
+    u32x2 w2 = {pack_bf16(acc[k][0] * f, acc[k][1] * f), pack_bf16(acc[k][2] * f, acc[k][3] * f)};
     *reinterpret_cast<u32x2*>(op) = w2;
   }
 }
