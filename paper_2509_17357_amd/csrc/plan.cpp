@@ -122,27 +122,43 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
     wide_piece_keys = (int)std::min<double>(std::max<double>(keys, kMinPiece), 1 << 30);
     wide_piece_keys = (wide_piece_keys + kWideKvTile - 1) / kWideKvTile * kWideKvTile;
   }
+  const long long target_items = std::max(n_cus, 1);  // about one span per CU: longer spans mean fewer work-group starts and fewer partial results to merge (measured: 6 % on the Llama-3-8B-shaped batch against four per CU)
+  long long span = (narrow_keys + target_items - 1) / target_items;
+  span = (span + kNarrowKvStep - 1) / kNarrowKvStep * kNarrowKvStep;
+  constexpr int kMaxSpanSteps = 16;  // spans are 2 .. 16 steps of kNarrowKvStep keys
+  span = std::min<long long>(std::max<long long>(span, 2 * kNarrowKvStep), kMaxSpanSteps * kNarrowKvStep);
+
   // A launch with few wide tiles (the paper's own iteration: one chunk of at most 512 tokens
   // = 64 tiles, section 5.1) lives or dies by how its spans pack onto the CUs: 64 tiles in
-  // five spans each are 320 items for 256 CUs, two rounds where four spans each need one.
+  // five spans each are 320 items for 256 CUs, two rounds where four spans each need one, and
+  // with three spans each a quarter of the CUs stay free for the decodes meanwhile.
   // Such a launch therefore picks its span length by estimated duration: for every way of
   // cutting the longest tile into 1 .. 12 equal spans, the items and their times under a
-  // cost model fitted to per-work-group timestamps, scheduled as rounds over the CUs with
-  // the narrow items as filler, plus what the merge of the partial results costs.
+  // cost model fitted to measured launches; the wide items run in rounds over the CUs; the
+  // CUs that the last round leaves free take narrow items meanwhile, the narrow items left
+  // after that follow in rounds of their own; plus what the merge of the partial results costs.
   if (wide_cost_total > 0 && wide_tiles <= 2LL * std::max(n_cus, 1)) {
     const int cus = std::max(n_cus, 1);
-    // microseconds on MI355X (D = 128, bf16): a wide item that covers a span takes about
-    // 16 + 0.0223 per key at 256 rows (three quarters of that per key at half height), a
-    // narrow span 8 + 0.0096 per key; a partial slot costs the merge about 9 ns
-    const double wide_us0 = 16.0, wide_us_key = 0.0223, narrow_us0 = 8.0, narrow_us_key = 0.0096, slot_us = 0.009;
-    long long longest = 0;
+    // microseconds on MI355X (D = 128, bf16), fitted to 41 launches (8 paper-shaped iterations
+    // of 2 k .. 64 k context x the cuts that give distinct plans): a wide item takes
+    // 12 + 0.0237 per key at 256 rows (three quarters of that per key at half height), a
+    // narrow span 6 + 0.0159 per key; a partial slot costs the merge 6 ns, its launch 4 us
+    const double wide_us0 = 12.0, wide_us_key = 0.0237, narrow_us0 = 6.0, narrow_us_key = 0.0159, slot_us = 0.006,
+                 merge_launch_us = 4.0;
+    long long longest = 0, n_narrow = 0;
     for (int s = 0; s < n_seqs; ++s) {
       const long long P = prefix_lens[s], C = chunk_lens[s];
-      if (C * group > kNarrowRows) longest = std::max(longest, P + C);
+      if (C <= 0) continue;
+      const long long copies = (long long)Hkv * n_groups;
+      if (C * group > kNarrowRows) {
+        longest = std::max(longest, P + C);
+        const long long rem = C % wide_tok;
+        if (rem && rem * group <= kNarrowRows) n_narrow += std::max<long long>(1, (P + C + span - 1) / span) * copies;
+      } else {
+        n_narrow += std::max<long long>(1, (P + C + span - 1) / span) * copies;
+      }
     }
-    const double narrow_us = narrow_keys > 0
-        ? narrow_us_key * (double)narrow_keys + narrow_us0 * std::max<double>(1.0, (double)narrow_keys / 2048.0)
-        : 0.0;
+    const double narrow_item_us = n_narrow > 0 ? narrow_us0 + narrow_us_key * (double)narrow_keys / (double)n_narrow : 0.0;
     double best_us = 0;
     int best_piece = 0;
     for (int cut = 1; cut <= 12; ++cut) {
@@ -172,9 +188,15 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
       }
       if (items == 0) break;
       const long long rounds = (items + cus - 1) / cus;
-      const double wide_us = (double)(rounds - 1) * (total_us / (double)items) + longest_us;
-      const double fluid_us = (total_us + narrow_us) / cus;
-      const double us = std::max(wide_us, fluid_us) + slot_us * (double)slots + (slots ? 4.0 : 0.0);
+      const long long last_round = items - (rounds - 1) * cus;
+      const double mean_us = total_us / (double)items;
+      double us = (double)(rounds - 1) * mean_us + longest_us;
+      if (n_narrow > 0) {
+        const long long absorbed = (cus - last_round) * (long long)(mean_us / narrow_item_us);
+        const long long left = std::max<long long>(0, n_narrow - absorbed);
+        us += (double)((left + cus - 1) / cus) * narrow_item_us;
+      }
+      us += slot_us * (double)slots + (slots ? merge_launch_us : 0.0);
       if (best_piece == 0 || us < best_us) {
         best_us = us;
         best_piece = piece;
@@ -182,12 +204,6 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
     }
     if (best_piece > 0) wide_piece_keys = best_piece;
   }
-  const long long target_items = std::max(n_cus, 1);  // about one span per CU: longer spans mean fewer work-group starts and fewer partial results to merge (measured: 6 % on the Llama-3-8B-shaped batch against four per CU)
-  long long span = (narrow_keys + target_items - 1) / target_items;
-  span = (span + kNarrowKvStep - 1) / kNarrowKvStep * kNarrowKvStep;
-  constexpr int kMaxSpanSteps = 16;  // spans are 2 .. 16 steps of kNarrowKvStep keys
-  span = std::min<long long>(std::max<long long>(span, 2 * kNarrowKvStep), kMaxSpanSteps * kNarrowKvStep);
-
   Scratch& sc = scratch();
   sc.seqs.resize((size_t)n_seqs);
   sc.wide.clear();

@@ -118,6 +118,22 @@ def test_plan_queues_follow_xcd_order():
             if key in last:
                 assert it[F["q_tok0"]] < last[key]        # the latest tile (the most keys) first
             last[key] = int(it[F["q_tok0"]])
+    # a queue's runs (tiles of one (sequence, KV head), back to back) come in the order of their
+    # shortest tile, longest first: the wide items that start last are the queue's shortest
+    for x in range(8):
+        runs = []   # [key, fewest keys of the run]
+        for xx, it in wide:
+            if xx != x:
+                continue
+            key = (int(it[F["seq"]]), int(it[F["kv_head"]]))
+            n_keys = int(it[F["kv_end"]] - it[F["kv_begin"]])
+            if runs and runs[-1][0] == key:
+                runs[-1][1] = min(runs[-1][1], n_keys)
+            else:
+                runs.append([key, n_keys])
+        assert len(runs) >= 2
+        shortest = [r[1] for r in runs]
+        assert shortest == sorted(shortest, reverse=True), shortest
     # the eight queues carry similar amounts of work
     load = np.zeros(8)
     for it in items:
