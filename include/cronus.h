@@ -154,7 +154,8 @@ int cronus_attn_mixed(const cronus_kv_cache* cache, const void* q, void* out,
  * that the library runs on holds its own copy until the process ends); the work list reaches
  * it as kernel arguments of small upload launches (about one per 48 work items) on
  * `hip_stream`.  The first call on a device looks up that device's address of the array and
- * sets the kernels' attributes (no allocation either).
+ * sets the kernels' attributes (no allocation either).  On the host the planner keeps its
+ * per-thread arrays (ordinary heap memory, grown to the largest batch the thread has planned).
  *   - CRONUS_ERR_WORKSPACE, nothing enqueued: the batch's plan image plus partial results
  *     exceed the array (about 4000 partial slots at head_dim 128; every benchmark batch fits).
  *   - fp8 cache: no bf16 copy is made (it would not fit); chunks of many tiles convert codes on

@@ -1219,7 +1219,9 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(AttnParams p)
   const size_t step = slot * (size_t)mi.stride;
   const float vmul = FP8 ? p.v_scale[mi.kv_head] : 1.0f;
   const float* base = p.partials + (size_t)mi.first_partial * slot;
-  int row[NPASS];  // clamped: rows past the item's last repeat it (loaded, never stored)
+  // pass k covers rows k * RPP ..; a pass past the item's last row is skipped as a whole
+  // (decodes have G rows), inside a pass the rows past the last repeat it (loaded, never stored)
+  int row[NPASS];
 #pragma unroll
   for (int k = 0; k < NPASS; ++k) row[k] = min((int)threadIdx.x / TPR + k * RPP, mi.n_rows - 1);
   float mt[NPASS];
@@ -1227,7 +1229,8 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(AttnParams p)
   for (int k = 0; k < NPASS; ++k) mt[k] = kNeg * 4.f;
   for (int s = 0; s < mi.n_split; ++s) {
 #pragma unroll
-    for (int k = 0; k < NPASS; ++k) mt[k] = fmaxf(mt[k], base[s * step + kNarrowRows * D + row[k]]);
+    for (int k = 0; k < NPASS; ++k)
+      if (k * RPP < mi.n_rows) mt[k] = fmaxf(mt[k], base[s * step + kNarrowRows * D + row[k]]);
   }
   f32x4 acc[NPASS];
   float ls[NPASS];
@@ -1242,9 +1245,15 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(AttnParams p)
     f32x4 o4[NPASS];
 #pragma unroll
     for (int k = 0; k < NPASS; ++k) {
-      ms[k] = ps[kNarrowRows * D + row[k]];
-      o4[k] = *reinterpret_cast<const f32x4*>(ps + row[k] * D + 4 * dq);
-      lsp[k] = ps[kNarrowRows * D + kNarrowRows + row[k]];
+      if (k * RPP < mi.n_rows) {
+        ms[k] = ps[kNarrowRows * D + row[k]];
+        o4[k] = *reinterpret_cast<const f32x4*>(ps + row[k] * D + 4 * dq);
+        lsp[k] = ps[kNarrowRows * D + kNarrowRows + row[k]];
+      } else {
+        ms[k] = 0.f;
+        o4[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+        lsp[k] = 0.f;
+      }
     }
 #pragma unroll
     for (int k = 0; k < NPASS; ++k) {
