@@ -190,17 +190,14 @@ int cronus_attn_mixed_plan_stats(const cronus_kv_cache* cache, const int32_t* pr
 
 /*
  * cronus_attn_mixed_plan_items - the work list itself, for inspection and tests (host
- * only, nothing is launched).  Writes up to `capacity` items, 13 int32 each: seq, kv_head,
- * head0, n_heads, q_tok0, n_tok, kv_begin, kv_end, partial, wide, pair_tok1, pair_ntok,
- * queue.  The items form 8 queues, listed one after the other, each in the order in which
+ * only, nothing is launched).  Writes up to `capacity` items, 11 int32 each: seq, kv_head,
+ * head0, n_heads, q_tok0, n_tok, kv_begin, kv_end, partial, wide, queue.  The items form 8 queues, listed one after the other, each in the order in which
  * its items are taken: the main kernel's work-groups stay resident (one per CU) and take
  * items from the queue of the XCD they run on, then from the other queues.  wide >= 1: chunk
  * tile over keys [kv_begin, kv_end) (wide >= 2, fp8 cache only: it reads the launch's bf16
  * copy of its sequence, whose first block there is wide - 2); wide = 0: narrow item over
  * keys [kv_begin, kv_end); partial >= 0 when the item's result is merged with other spans
- * of the same rows.  pair_tok1 > 0 (wide items of launches with many tiles per CU): the same
- * work-group then also computes the earlier tile of pair_ntok tokens that starts at chunk
- * token pair_tok1 - 1, against all keys up to that tile's causal end.  Returns the number
+ * of the same rows.  Returns the number
  * of items of the plan (which may exceed capacity), or a negative cronus_status on invalid
  * arguments.  items may be NULL when capacity = 0.
  */

@@ -236,11 +236,11 @@ def cronus_attn_mixed_plan_stats(cache: cronus_kv_cache, prefix_lens, chunk_lens
 
 
 PLAN_ITEM_FIELDS = ("seq", "kv_head", "head0", "n_heads", "q_tok0", "n_tok", "kv_begin", "kv_end", "partial", "wide",
-                    "pair_tok1", "pair_ntok", "queue")
+                    "queue")
 
 
 def cronus_attn_mixed_plan_items(cache: cronus_kv_cache, prefix_lens, chunk_lens) -> np.ndarray:
-    """The work list as an int32 array [n_items, 13] (columns: PLAN_ITEM_FIELDS), queue by queue."""
+    """The work list as an int32 array [n_items, 11] (columns: PLAN_ITEM_FIELDS), queue by queue."""
     p, pp = _host_i32(prefix_lens)
     c, cp = _host_i32(chunk_lens)
     n = lib().cronus_attn_mixed_plan_items(ctypes.byref(cache), pp, cp, int(p.size), None, 0)

@@ -203,9 +203,9 @@ int64_t cronus_attn_mixed_plan_items(const cronus_kv_cache* cache, const int32_t
   for (int64_t i = 0; i < n; ++i) {
     while (queue + 1 < kQueues && i >= plan.q_base[queue] + plan.q_len[queue]) ++queue;
     const WorkItem& w = wi[i];
-    const int32_t row[13] = {w.seq, w.kv_head, w.head0, w.n_heads, w.q_tok0, w.n_tok, w.kv_begin, w.kv_end,
-                             w.partial, w.wide, w.pair_tok1, w.pair_ntok, queue};
-    std::memcpy(items + 13 * i, row, sizeof(row));
+    const int32_t row[11] = {w.seq, w.kv_head, w.head0, w.n_heads, w.q_tok0, w.n_tok, w.kv_begin, w.kv_end,
+                             w.partial, w.wide, queue};
+    std::memcpy(items + 11 * i, row, sizeof(row));
   }
   return plan.n_items;
 }

@@ -1133,22 +1133,11 @@ __global__ __launch_bounds__(kThreads) void attn_mixed_kernel(AttnParams p) {
     if (it.wide < 0) break;
     if (it.n_tok <= 0 || it.n_heads <= 0) continue;
     if (it.wide) {
-      // the tile itself, then the earlier tile paired with it (if any): keys from 0, final output
-      WorkItem cur = it;
-      for (int rep = 0;; ++rep) {
-        if constexpr (FP8) {
-          if (cur.wide >= 2) run_wide_dma<D, true>(p, cur, smem);
-          else run_wide_staged<D, FP8, 1>(p, cur, smem);
-        } else {
-          run_wide_dma<D, false>(p, cur, smem);
-        }
-        if (rep || it.pair_tok1 <= 0) break;
-        cur.q_tok0 = it.pair_tok1 - 1;
-        cur.n_tok = it.pair_ntok;
-        cur.kv_begin = 0;
-        cur.kv_end = it.prefix_len + cur.q_tok0 + cur.n_tok;
-        cur.partial = -1;
-        __syncthreads();  // every wave is done with the first tile's LDS stages
+      if constexpr (FP8) {
+        if (it.wide >= 2) run_wide_dma<D, true>(p, it, smem);
+        else run_wide_staged<D, FP8, 1>(p, it, smem);
+      } else {
+        run_wide_dma<D, false>(p, it, smem);
       }
     } else {
       run_narrow<D, FP8>(p, it, smem);

@@ -45,11 +45,7 @@ struct WorkItem {
   // copy of the sequence's record, so that a work-group needs one dependent load less
   // before it can address Q and the block table
   int32_t prefix_len, chunk_len, q_off, n_blocks;
-  // A wide item may carry a second, earlier tile of the same (sequence, KV head, head
-  // group), which the work-group computes after this one: tokens pair_tok1 - 1 ..
-  // pair_tok1 - 2 + pair_ntok against keys [0, prefix_len + that tile's end), always
-  // whole (never a span).  pair_tok1 = 0: none.
-  int32_t pair_tok1, pair_ntok;
+  int32_t reserved[2];  // zero
 };
 static_assert(sizeof(WorkItem) == 64, "one work item = one 64-byte line");
 

@@ -105,13 +105,6 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
       wide_tiles += (full + (rem && rem * group > kNarrowRows)) * Hkv * n_groups;
     }
   }
-  // With many tiles per CU (whole prompts, prefix_len = 0, rather than continuation chunks)
-  // the fixed cost of an item weighs most on the short early tiles.  One work-group then
-  // takes the i-th and the (n-1-i)-th tile of a (sequence, KV head): half as many
-  // work-group starts, and items of one sequence cost the same.  Kept for launches that
-  // still have kPairMinPerCu items per CU afterwards, where packing stays fine-grained.
-  constexpr int kPairMinPerCu = 8;
-  const bool pair_tiles = wide_tiles >= 2LL * kPairMinPerCu * std::max(n_cus, 1);
   // no wide item should hold a CU for much longer than three quarters of a CU's fair share
   // (measured on paper-shaped iterations: smaller spans pay more for their prologue and the
   // merge than they gain in balance), and no span is shorter than 16 K/V tiles
@@ -319,22 +312,6 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
             g.cost += cost;
           }
           g.end = (int32_t)sc.wide.size();
-          if (pair_tiles && max_split == 1 && g.end - g.begin >= 2) {
-            // (tiles cut into spans stay single)
-            // tiles were generated shortest first: the k-th longest takes the k-th shortest
-            const int n = g.end - g.begin, n_pairs = n / 2;
-            for (int k = 0; k < n_pairs; ++k) {
-              WorkItem& big = sc.wide[(size_t)(g.end - 1 - k)];
-              const WorkItem& small = sc.wide[(size_t)(g.begin + k)];
-              big.pair_tok1 = small.q_tok0 + 1;
-              big.pair_ntok = small.n_tok;
-              sc.wide_cost[(size_t)(g.end - 1 - k)] += sc.wide_cost[(size_t)(g.begin + k)];
-            }
-            // drop the tiles that travel as seconds; the rest keeps its ascending order
-            sc.wide.erase(sc.wide.begin() + g.begin, sc.wide.begin() + g.begin + n_pairs);
-            sc.wide_cost.erase(sc.wide_cost.begin() + g.begin, sc.wide_cost.begin() + g.begin + n_pairs);
-            g.end -= n_pairs;
-          }
           if (g.end > g.begin) sc.groups.push_back(g);
         }
       }

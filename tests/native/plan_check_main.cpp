@@ -7,7 +7,7 @@
 //
 //   plan <Hq> <Hkv> <D> <fp8:0|1> <n_cus> <allow_stage:0|1> <n_seqs> P0 C0 P1 C1 ...
 //     -> "plan <rc> <n_items> <n_wide> <n_partials> <n_merge> <n_merge_rows> <n_stage_blocks>
-//              <total_bytes> <image_bytes>", then n_items lines "i" with the 13 item fields,
+//              <total_bytes> <image_bytes>", then n_items lines "i" with the 11 item fields,
 //        then n_merge lines "m" with the 12 merge fields
 //   split <l_in> <n_d> <l_ctxd> <n_free> <k_p> <b_p> <k_ctxp> <k_ctxd> <b_c> <n_size> <B> <n_cand>
 //     -> "split <rc> <l_p> <t_prefill> <t_chunked>"
@@ -53,8 +53,8 @@ int main() {
       for (int64_t i = 0; i < plan.n_items; ++i) {
         while (queue + 1 < cronus::kQueues && i >= plan.q_base[queue] + plan.q_len[queue]) ++queue;
         const cronus::WorkItem& w = wi[i];
-        std::printf("i %d %d %d %d %d %d %d %d %d %d %d %d %d\n", w.seq, w.kv_head, w.head0, w.n_heads, w.q_tok0, w.n_tok,
-                    w.kv_begin, w.kv_end, w.partial, w.wide, w.pair_tok1, w.pair_ntok, queue);
+        std::printf("i %d %d %d %d %d %d %d %d %d %d %d\n", w.seq, w.kv_head, w.head0, w.n_heads, w.q_tok0, w.n_tok,
+                    w.kv_begin, w.kv_end, w.partial, w.wide, queue);
       }
       const auto* mi = reinterpret_cast<const cronus::MergeItem*>(image.data() + plan.off_merge);
       for (int64_t i = 0; i < plan.n_merge; ++i) {

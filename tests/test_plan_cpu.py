@@ -39,14 +39,8 @@ def verify_items(shape, P, C, items, stats):
     cover = {}
     tiles = []
     for it in real:
-        s, kvh, h0, nh, t0, nt, kb, ke, part, wide, pair1, pair_nt = (int(x) for x in it[:12])
+        s, kvh, h0, nh, t0, nt, kb, ke, part, wide = (int(x) for x in it[:10])
         tiles.append((s, kvh, h0, nh, t0, nt, kb, ke, part, wide))
-        if pair1:
-            # the second tile of a work-group: earlier tokens of the same heads, whole, final
-            assert wide >= 1 and part == -1 and kb == 0 and 0 <= pair1 - 1 < t0 and pair_nt * nh > 32
-            tiles.append((s, kvh, h0, nh, pair1 - 1, pair_nt, 0, int(P[s]) + pair1 - 1 + pair_nt, -1, wide))
-        else:
-            assert pair_nt == 0
     for s, kvh, h0, nh, t0, nt, kb, ke, part, wide in tiles:
         assert 0 <= s < len(P) and C[s] > 0 and 0 <= kvh < shape.n_kv_heads
         assert h0 // G == kvh and (h0 + nh - 1) // G == kvh and nh >= 1   # heads of one KV head
@@ -161,33 +155,19 @@ def test_few_long_wide_tiles_are_split_over_keys():
     assert (w3[:, F["kv_begin"]] == 0).all() and (w3[:, F["partial"]] == -1).all()
 
 
-def test_many_tiles_per_cu_are_paired():
-    """Whole prompts (prefix 0) with 16 or more tiles per CU: a work-group takes the i-th and
-    the (n-1-i)-th tile of a (sequence, KV head), so the items of one sequence cost the same
-    and there are half as many; continuation chunks with 8 tiles per CU stay single."""
+def test_whole_prompts_with_many_tiles_per_cu():
+    """Whole prompts (prefix 0) with 16 tiles per CU: one item per tile, none cut into spans;
+    a (sequence, KV head)'s tiles sit in one run, longest first."""
     sh = W.HeadShape(32, 8, 128)
     P, C = [0] * 8, [4096] * 8                      # 8 x 64 tiles x 8 KV heads = 4096 tiles, 16 per CU
     items, stats = plan_for(sh, P, C)
     wide = items[items[:, F["wide"]] >= 1]
-    assert stats["wide_items"] == 2048 and len(wide) == 2048 and (wide[:, F["pair_tok1"]] > 0).all()
-    first = wide[:, F["q_tok0"]] // 64
-    second = (wide[:, F["pair_tok1"]] - 1) // 64
-    assert ((first + second) == 63).all() and (wide[:, F["pair_ntok"]] == 64).all()
-    # every (sequence, KV head, tile) exactly once, as a first or as a second tile
-    key = lambda t: (wide[:, F["seq"]] * 8 + wide[:, F["kv_head"]]) * 64 + t
-    seen = np.concatenate([key(first), key(second)])
-    assert len(np.unique(seen)) == 4096 == len(seen)
-    # the keys of both tiles of an item add up to a constant
-    assert (wide[:, F["kv_end"]] + wide[:, F["pair_tok1"]] - 1 + 64 == 4096 + 64).all()
-    # an odd number of tiles leaves the middle one single; small cases go through the full check
+    assert stats["wide_items"] == 4096 and len(wide) == 4096 == len(items)
+    assert (wide[:, F["partial"]] == -1).all() and (wide[:, F["kv_begin"]] == 0).all()
+    key = (wide[:, F["seq"]] * 8 + wide[:, F["kv_head"]]) * 64 + wide[:, F["q_tok0"]] // 64
+    assert len(np.unique(key)) == 4096
+    assert (wide[:, F["kv_end"]] == wide[:, F["q_tok0"]] + wide[:, F["n_tok"]]).all()
     check_plan(sh, [0] * 16, [64 * 33] * 16)
-    items, _ = plan_for(sh, [0] * 16, [64 * 33] * 16)
-    wide = items[items[:, F["wide"]] >= 1]
-    assert (wide[:, F["pair_tok1"]] == 0).sum() == 16 * 8
-    # the benchmark batches keep single tiles (8 tiles per CU)
-    b = W.draw_batch(3)
-    items, _ = plan_for(b.shape, b.prefix_lens, b.chunk_lens)
-    assert (items[:, F["pair_tok1"]] == 0).all()
 
 
 def test_small_launches_take_half_tiles():
@@ -248,7 +228,7 @@ def test_fp8_chunks_of_many_tiles_read_a_bf16_copy():
 def test_plan_random_batches_cover_every_row_once(seed):
     """Seeded random batches over head shapes, cache types and length mixes (empty sequences,
     decodes, short and long chunks, long prefixes): the coverage and alignment invariants of
-    check_plan hold whatever mix of tile sizes, key spans, pairs and copies the planner picks."""
+    check_plan hold whatever mix of tile sizes, key spans and copies the planner picks."""
     rng = np.random.default_rng([seed, 0x91A])
     shape = [W.HeadShape(32, 8, 128), W.HeadShape(28, 4, 128), W.HeadShape(8, 2, 64), W.HeadShape(64, 8, 128, "fp8"),
              W.HeadShape(16, 16, 64), W.HeadShape(64, 1, 128), W.HeadShape(16, 2, 128, "fp8")][seed % 7]

@@ -64,7 +64,7 @@ def run_cases(exe, lines):
             replies.append({"rc": int(f[1]), "l_p": int(f[2]), "tp": float(f[3]), "tc": float(f[4])})
     for rep in replies:
         if "items" in rep:
-            rep["items"] = np.array(rep["items"], dtype=np.int32).reshape(-1, 13)
+            rep["items"] = np.array(rep["items"], dtype=np.int32).reshape(-1, 11)
     return replies
 
 
@@ -96,7 +96,7 @@ def threshold_cases():
             ([511 + x], [1]), ([255 + x], [1]),  # span granularity
             ([2 ** 20 + x], [1]),                # a million keys
         ]
-    cases += [([0] * 32, [64 * 16] * 32), ([0] * 31, [64 * 16] * 31),   # 16 tiles per CU at 256 CUs: paired or not
+    cases += [([0] * 32, [64 * 16] * 32), ([0] * 31, [64 * 16] * 31),   # 16 tiles per CU at 256 CUs
               ([200000, 200000, 100], [1024, 1024, 1024])]              # fp8 copy: the second sequence would pass the 1 GiB cap at Hkv = 8
     return cases
 
