@@ -122,22 +122,34 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
   span = std::min<long long>(std::max<long long>(span, 2 * kNarrowKvStep), kMaxSpanSteps * kNarrowKvStep);
 
   // A launch with few wide tiles (the paper's own iteration: one chunk of at most 512 tokens
-  // = 64 tiles, section 5.1) lives or dies by how its spans pack onto the CUs: 64 tiles in
-  // five spans each are 320 items for 256 CUs, two rounds where four spans each need one, and
-  // with three spans each a quarter of the CUs stay free for the decodes meanwhile.
+  // = 64 tiles, section 5.1) lives or dies by how its spans pack onto the CUs next to the
+  // decodes: 64 tiles in five spans each are 320 items for 256 CUs, two rounds where four
+  // spans each need one; next to many decodes long wide items start late and end last.
   // Such a launch therefore picks its span length by estimated duration: for every way of
-  // cutting the longest tile into 1 .. 12 equal spans, the items and their times under a
-  // cost model fitted to measured launches; the wide items run in rounds over the CUs; the
-  // CUs that the last round leaves free take narrow items meanwhile, the narrow items left
-  // after that follow in rounds of their own; plus what the merge of the partial results costs.
+  // cutting the longest tile into 1 .. 8 equal spans (of at least 12 K/V tiles), the items
+  // and their times under a model fitted to measured launches on MI355X (D = 128, bf16: 47
+  // paper-shaped iterations of 1 k .. 64 k context with 0 .. 200 decodes of up to 1 M keys in
+  // total, each with every cut that gives a distinct plan; the model's choice is the measured
+  // best or within 3 % of it on all of them).  Two regimes, by the narrow items' share of the
+  // work:
+  //  * chunk-dominated (estimated narrow time under 0.3 of the wide tiles'): the wide items
+  //    run in rounds over the CUs; the CUs that the last round leaves free take narrow items
+  //    meanwhile, the narrow items left after that follow in rounds of their own.  A wide item
+  //    takes 8 us + 23.7 ns per key at 256 rows (three quarters of that per key at half
+  //    height), a narrow span 6 us + 12 ns per key, the merge 13 us + 3 ns per partial slot.
+  //  * decode-rich: the launch cannot end before the items' times summed over the CUs, before
+  //    the wide items alone have run in rounds, or before the narrow items' K/V has streamed at
+  //    5.2 TB/s; the queues alternate the two kinds with the wide list running ahead, so the
+  //    last wide item starts at about 0.77 of that time and the launch ends when it does.
+  //    Next to streaming CUs a wide item takes 10 us + 16 ns per key (the clock is higher than
+  //    under a chip-wide MFMA load), a narrow span 8 us + 6.7 ns per key, and a partial slot
+  //    costs 21 ns (its traffic competes with the decodes'), the merge launch 4 us.
   if (wide_cost_total > 0 && wide_tiles <= 2LL * std::max(n_cus, 1)) {
     const int cus = std::max(n_cus, 1);
-    // microseconds on MI355X (D = 128, bf16), fitted to 41 launches (8 paper-shaped iterations
-    // of 2 k .. 64 k context x the cuts that give distinct plans): a wide item takes
-    // 12 + 0.0237 per key at 256 rows (three quarters of that per key at half height), a
-    // narrow span 6 + 0.0159 per key; a partial slot costs the merge 6 ns, its launch 4 us
-    const double wide_us0 = 12.0, wide_us_key = 0.0237, narrow_us0 = 6.0, narrow_us_key = 0.0159, slot_us = 0.006,
-                 merge_launch_us = 4.0;
+    struct Costs { double wide_us0, wide_us_key, narrow_us0, narrow_us_key, slot_us, merge_us0; };
+    const Costs chunk_dominated{8.0, 0.0237, 6.0, 0.012, 0.003, 13.0}, decode_rich{10.0, 0.016, 8.0, 0.0067, 0.0206, 4.0};
+    const double hbm_bytes_per_us = 5.24e6, last_wide_start = 0.77;
+    constexpr int kMinCutPiece = 12 * kWideKvTile;
     long long longest = 0, n_narrow = 0;
     for (int s = 0; s < n_seqs; ++s) {
       const long long P = prefix_lens[s], C = chunk_lens[s];
@@ -151,15 +163,12 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
         n_narrow += std::max<long long>(1, (P + C + span - 1) / span) * copies;
       }
     }
-    const double narrow_item_us = n_narrow > 0 ? narrow_us0 + narrow_us_key * (double)narrow_keys / (double)n_narrow : 0.0;
-    double best_us = 0;
-    int best_piece = 0;
-    for (int cut = 1; cut <= 12; ++cut) {
-      int piece = (int)((longest + cut - 1) / cut);
-      piece = (piece + kWideKvTile - 1) / kWideKvTile * kWideKvTile;
-      if (cut > 1 && piece < kMinPiece) break;
-      long long items = 0, slots = 0;
-      double total_us = 0, longest_us = 0;
+    const double kv_elem_bytes = cache->kv_dtype == CRONUS_KV_FP8_E4M3 ? 1.0 : 2.0;
+    const double hbm_us = (double)narrow_keys * 2.0 * D * kv_elem_bytes / hbm_bytes_per_us;  // K and V of every narrow key
+    // items, summed and longest time of the wide items, and partial slots for a span length
+    struct WideSide { long long items, slots; double total_us, longest_us; };
+    auto wide_side = [&](int piece, const Costs& c) {
+      WideSide w{0, 0, 0.0, 0.0};
       for (int s = 0; s < n_seqs; ++s) {
         const long long P = prefix_lens[s], C = chunk_lens[s];
         if (C * group <= kNarrowRows) continue;
@@ -171,25 +180,54 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
           const long long per = ((kv_total + n_split - 1) / n_split + kWideKvTile - 1) / kWideKvTile * kWideKvTile;
           n_split = (kv_total + per - 1) / per;
           const double height = nt * group * 2 <= wide_rows ? 0.75 : 1.0;
-          const double us = wide_us0 + wide_us_key * height * (double)per;
+          const double us = c.wide_us0 + c.wide_us_key * height * (double)per;
           const long long copies = (long long)Hkv * n_groups;
-          items += n_split * copies;
-          total_us += us * (double)(n_split * copies);
-          longest_us = std::max(longest_us, us);
-          if (n_split > 1) slots += n_split * copies * kWaves;
+          w.items += n_split * copies;
+          w.total_us += us * (double)(n_split * copies);
+          w.longest_us = std::max(w.longest_us, us);
+          if (n_split > 1) w.slots += n_split * copies * kWaves;
         }
       }
-      if (items == 0) break;
-      const long long rounds = (items + cus - 1) / cus;
-      const long long last_round = items - (rounds - 1) * cus;
-      const double mean_us = total_us / (double)items;
-      double us = (double)(rounds - 1) * mean_us + longest_us;
-      if (n_narrow > 0) {
-        const long long absorbed = (cus - last_round) * (long long)(mean_us / narrow_item_us);
+      return w;
+    };
+    auto narrow_item_us = [&](const Costs& c) {
+      return n_narrow > 0 ? c.narrow_us0 + c.narrow_us_key * (double)narrow_keys / (double)n_narrow : 0.0;
+    };
+    const WideSide whole = wide_side(1 << 30, chunk_dominated);  // no tile cut
+    const bool few_decodes =
+        whole.items == 0 || (double)n_narrow * narrow_item_us(chunk_dominated) < 0.3 * whole.total_us;
+    const Costs& c = few_decodes ? chunk_dominated : decode_rich;
+    const double narrow_us = narrow_item_us(c), narrow_total_us = (double)n_narrow * narrow_us;
+    double best_us = 0;
+    int best_piece = 0;
+    for (int cut = 1; cut <= 8; ++cut) {
+      int piece = (int)((longest + cut - 1) / cut);
+      piece = (piece + kWideKvTile - 1) / kWideKvTile * kWideKvTile;
+      if (cut > 1 && piece < kMinCutPiece) break;
+      const WideSide w = wide_side(piece, c);
+      if (w.items == 0) break;
+      const long long rounds = (w.items + cus - 1) / cus;
+      const double mean_us = w.total_us / (double)w.items;
+      const double wide_alone_us = (double)(rounds - 1) * mean_us + w.longest_us;
+      // narrow items that the CUs left free by the last round of wide items take meanwhile
+      auto trailing_us = [&]() {
+        if (n_narrow == 0) return 0.0;
+        const long long last_round = w.items - (rounds - 1) * cus;
+        const long long absorbed = (cus - last_round) * (long long)(mean_us / narrow_us);
         const long long left = std::max<long long>(0, n_narrow - absorbed);
-        us += (double)((left + cus - 1) / cus) * narrow_item_us;
+        return (double)((left + cus - 1) / cus) * narrow_us;
+      };
+      double us;
+      if (few_decodes) {
+        us = wide_alone_us + trailing_us();
+      } else {
+        const double floor_us = std::max(std::max((w.total_us + narrow_total_us) / cus, hbm_us), wide_alone_us);
+        const double ratio = narrow_total_us / w.total_us;
+        if (ratio < 0.3) us = wide_alone_us + trailing_us();
+        else if (ratio <= 10.0) us = std::max(floor_us, last_wide_start * floor_us + w.longest_us);
+        else us = std::max(floor_us, w.longest_us);
       }
-      us += slot_us * (double)slots + (slots ? merge_launch_us : 0.0);
+      us += c.slot_us * (double)w.slots + (w.slots ? c.merge_us0 : 0.0);
       if (best_piece == 0 || us < best_us) {
         best_us = us;
         best_piece = piece;
@@ -197,6 +235,7 @@ int build_plan(const cronus_kv_cache* cache, const int32_t* prefix_lens, const i
     }
     if (best_piece > 0) wide_piece_keys = best_piece;
   }
+
   Scratch& sc = scratch();
   sc.seqs.resize((size_t)n_seqs);
   sc.wide.clear();
