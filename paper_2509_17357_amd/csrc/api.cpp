@@ -323,6 +323,6 @@ const char* cronus_status_string(int status) {
   }
 }
 
-int cronus_version(void) { return 503; }  // 0.5.3: resident work-groups with work queues; plan items carry their queue; MFMA probe
+int cronus_version(void) { return 504; }  // 0.5.4: resident work-groups with work queues; plan items carry their queue; MFMA probe
 
 }  // extern "C"
